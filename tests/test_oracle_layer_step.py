@@ -1,0 +1,193 @@
+"""Pins for the checker's layer step (Algorithm 1) and its two execution modes.
+
+The constructions make the quasi-hidden state coincide with the next layer's true router
+input, which fixes where d_l enters, which gates weight it and which layer's norm is used;
+the remaining tests pin the mode logic, the counters and the pairing of experts with gates."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2603_19289_amd import workload as W
+from tests.helpers import build, make_advance, oracle_model, small_workload
+
+
+def _run(model, wl, mode, x0, adv, **kw):
+    orc = O.MoEOracle(model, mode, wl.slots, **kw)
+    return orc, O.run_tokens(orc, x0, adv)
+
+
+def test_zero_default_vectors_zero_update_gives_hit_rate_one():
+    # d = 0, no residual noise and W_down = 0 (the block adds nothing): q_l is s_{l+1} bit for bit
+    wl = small_workload(n_layers=5, dtype="bf16", res_a=1.0, res_b=0.0, d_std=0.0)
+    res, ex, _ = build(wl)
+    H, I = wl.hidden, wl.inter
+    ex[:, :, 2 * I * H:] = 0
+    model = oracle_model(wl, res, ex)
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    spec, tr_s = _run(model, wl, O.MODE_SPECULATIVE, x0, adv)
+    ond, tr_o = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    assert spec.stats.predictions == wl.top_k * (wl.n_layers - 1) * wl.tokens
+    assert spec.stats.hits == spec.stats.predictions
+    for t in range(wl.tokens):
+        for l in range(wl.n_layers):
+            np.testing.assert_array_equal(tr_s[t][l][1].out, tr_o[t][l][1].out)
+            if l + 1 < wl.n_layers:
+                np.testing.assert_array_equal(tr_s[t][l][1].q, tr_s[t][l + 1][1].s)
+
+
+@pytest.mark.parametrize("dtype", ["f32"])
+def test_one_sample_default_vectors_make_q_equal_next_router_input(dtype):
+    # d_{l,e} := what expert e really outputs for this token, no noise: d_l = O_l, so
+    # r_l + d_l = r_{l+1} and q_l = LN_{l+1}(r_{l+1}) = s_{l+1}.  Gains differ per layer so that
+    # the wrong layer's norm, a d_l added after the norm, or d_l built from other gates all fail.
+    wl = small_workload(n_layers=4, dtype=dtype, tokens=1, res_a=1.0, res_b=0.0)
+    res, ex, model = build(wl, gains="random")
+    x0, _ = W.make_inputs(wl)
+
+    def adv(t, l, r, out):                     # exact r + O, no float32 stop
+        return r + out
+
+    dv = np.zeros((wl.n_layers, wl.n_experts, wl.hidden))           # float64 table
+    model.dvecs = dv
+    r = np.asarray(x0[0], dtype=np.float64)
+    for l in range(wl.n_layers):                                    # fill the table layer by layer
+        s = O.rmsnorm(r[0], model.rms_gain[l], model.rms_eps)
+        for e in range(wl.n_experts):
+            dv[l, e] = O.expert_ffn(*model.expert_mats(l, e), s, False)
+        orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots)
+        tr = O.run_tokens(orc, x0, adv, n_layers=l + 1)
+        r = adv(0, l, tr[0][l][0], tr[0][l][1].out)
+
+    spec, tr_s = _run(model, wl, O.MODE_SPECULATIVE, x0, adv)
+    ond, tr_o = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    assert spec.stats.hits == spec.stats.predictions == wl.top_k * (wl.n_layers - 1)
+    for l in range(wl.n_layers):
+        np.testing.assert_allclose(tr_s[0][l][1].out, tr_o[0][l][1].out, rtol=0, atol=1e-13)
+        if l + 1 < wl.n_layers:
+            np.testing.assert_allclose(tr_s[0][l][1].q, tr_s[0][l + 1][1].s, rtol=0, atol=1e-13)
+            np.testing.assert_allclose(tr_s[0][l][1].next_gates, tr_s[0][l + 1][1].true_gates, atol=1e-12)
+
+
+@pytest.mark.parametrize("bad", ["gain_of_wrong_layer", "uniform_gates", "d_after_norm", "dropped_d"])
+def test_planted_mistakes_in_the_quasi_hidden_state_are_caught(bad, monkeypatch):
+    # the construction above must tell these mistakes apart from the definition
+    wl = small_workload(n_layers=3, dtype="f32", tokens=1, res_a=1.0, res_b=0.0)
+    res, ex, model = build(wl, gains="random")
+    x0, _ = W.make_inputs(wl)
+    adv = lambda t, l, r, out: r + out
+    dv = np.zeros((wl.n_layers, wl.n_experts, wl.hidden))
+    model.dvecs = dv
+    r = np.asarray(x0[0], dtype=np.float64)
+    for l in range(wl.n_layers):
+        s = O.rmsnorm(r[0], model.rms_gain[l], model.rms_eps)
+        for e in range(wl.n_experts):
+            dv[l, e] = O.expert_ffn(*model.expert_mats(l, e), s, False)
+        tr = O.run_tokens(O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots), x0, adv, n_layers=l + 1)
+        r = adv(0, l, tr[0][l][0], tr[0][l][1].out)
+
+    good_q, good_d = O.quasi_hidden, O.layer_default_vector
+    if bad == "gain_of_wrong_layer":
+        gains = model.rms_gain
+        monkeypatch.setattr(O, "quasi_hidden", lambda r_, s_, d_, g_, eps, bf, fn=False:
+                            good_q(r_, s_, d_, gains[[np.array_equal(g_, gains[i]) for i in range(len(gains))].index(True) - 1], eps, bf, fn))
+    elif bad == "uniform_gates":
+        monkeypatch.setattr(O, "layer_default_vector", lambda dvl, ids, g: good_d(dvl, ids, np.full(len(g), 1 / len(g))))
+    elif bad == "d_after_norm":
+        monkeypatch.setattr(O, "quasi_hidden", lambda r_, s_, d_, g_, eps, bf, fn=False: O.rmsnorm(r_, g_, eps) + d_)
+    else:
+        monkeypatch.setattr(O, "layer_default_vector", lambda dvl, ids, g: 0 * good_d(dvl, ids, g))
+    _, tr_s = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    worst = max(np.abs(tr_s[0][l][1].q - tr_s[0][l + 1][1].s).max() for l in range(wl.n_layers - 1))
+    assert worst > 1e-4
+
+
+@pytest.mark.parametrize("dtype,B", [("f32", 1), ("bf16", 1), ("bf16", 3)])
+def test_mode_logic_counters_and_gate_pairing(dtype, B):
+    wl = small_workload(n_layers=4, dtype=dtype, batch=B, tokens=5, slots=4)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    spec, tr_s = _run(model, wl, O.MODE_SPECULATIVE, x0, adv)
+    ond, tr_o = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    k, L, T = wl.top_k, wl.n_layers, wl.tokens
+    F = torch.nn.functional
+    recount = 0
+    for t in range(T):
+        # layer 0 is a cold start: identical in both modes
+        np.testing.assert_array_equal(tr_s[t][0][1].out, tr_o[t][0][1].out)
+        np.testing.assert_array_equal(tr_s[t][0][1].exec_ids, tr_s[t][0][1].true_ids)
+        assert tr_s[t][L - 1][1].next_ids is None                 # nothing to predict after the last layer
+        for l in range(L):
+            rs, ro = tr_s[t][l][1], tr_o[t][l][1]
+            np.testing.assert_array_equal(ro.exec_ids, ro.true_ids)          # on-demand executes the routed set
+            np.testing.assert_allclose(rs.true_gates.sum(-1), 1.0, atol=1e-15)
+            if l > 0:
+                prev = tr_s[t][l - 1][1]
+                np.testing.assert_array_equal(rs.exec_ids, prev.next_ids)    # speculated experts ...
+                np.testing.assert_array_equal(rs.exec_gates, prev.next_gates)  # ... with their predicted gates
+                for b in range(B):
+                    recount += len(set(prev.next_ids[b].tolist()) & set(rs.true_ids[b].tolist()))
+            # output = sum over executed experts of (its gate) * SwiGLU on the TRUE s_l (library arithmetic)
+            for b in range(B):
+                s = torch.from_numpy(rs.s[b])
+                want = torch.zeros(wl.hidden, dtype=torch.float64)
+                for j in range(k):
+                    wg, wu, wd = (torch.from_numpy(O.decode_weights(m)) for m in model.expert_mats(l, int(rs.exec_ids[b, j])))
+                    h = F.silu(F.linear(s, wg)) * F.linear(s, wu)
+                    if dtype == "bf16":
+                        h = torch.from_numpy(O.bf16_round(h.numpy()))
+                    want += rs.exec_gates[b, j] * F.linear(h, wd)
+                np.testing.assert_allclose(rs.out[b], want.numpy(), rtol=1e-10, atol=1e-14)
+    assert spec.stats.predictions == k * B * (L - 1) * T
+    assert 0 <= spec.stats.hits <= spec.stats.predictions
+    assert spec.stats.hits == recount
+    assert 0 < spec.stats.hits < spec.stats.predictions            # the random workload is neither trivial case
+    assert spec.stats.tokens == ond.stats.tokens == T
+    assert spec.stats.layer_steps == ond.stats.layer_steps == L * T
+    for st in (spec.stats, ond.stats):
+        assert st.h2d_bytes == st.cache_misses * wl.expert_bytes
+    if B == 1:
+        assert ond.stats.cache_hits + ond.stats.cache_misses == k * L * T
+        assert spec.stats.cache_hits + spec.stats.cache_misses == k * L * T
+
+
+def test_router_input_is_rounded_to_bf16_only_in_bf16_mode():
+    for dtype in ("f32", "bf16"):
+        wl = small_workload(dtype=dtype, tokens=1)
+        res, ex, model = build(wl)
+        x0, eps = W.make_inputs(wl)
+        _, tr = _run(model, wl, O.MODE_ON_DEMAND, x0, make_advance(wl, eps))
+        s = tr[0][0][1].s
+        assert np.array_equal(s, O.bf16_round(s)) == (dtype == "bf16")
+
+
+def test_wave_execution_requests_when_the_union_exceeds_the_pool():
+    # B*k distinct experts can exceed S: the union is served in waves of S; only wave 0 of a
+    # prediction is requested one layer early, later waves when their turn comes
+    wl = small_workload(n_layers=3, dtype="f32", batch=4, tokens=3, slots=2, n_experts=8, top_k=2)
+    res, ex, model = build(wl)
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    for mode in (O.MODE_ON_DEMAND, O.MODE_SPECULATIVE):
+        orc, tr = _run(model, wl, mode, x0, adv)
+        expect = 0
+        for t in range(wl.tokens):
+            for l in range(wl.n_layers):
+                expect += len(set(tr[t][l][1].exec_ids.reshape(-1).tolist()))
+        # every executed expert is requested exactly once per layer step; in speculative mode the
+        # prefetch of wave 0 happens during the previous step but is still one request per expert
+        assert orc.stats.cache_hits + orc.stats.cache_misses == expect
+        assert sum(p.clock for p in orc.pools) >= wl.tokens * wl.n_layers
+
+
+def test_step_order_is_enforced_and_slots_must_cover_k():
+    wl = small_workload()
+    res, ex, model = build(wl)
+    with pytest.raises(ValueError):
+        O.MoEOracle(model, O.MODE_ON_DEMAND, wl.top_k - 1)
+    orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots)
+    orc.begin_token()
+    with pytest.raises(RuntimeError):
+        orc.layer_step(1, np.zeros((1, wl.hidden)))
