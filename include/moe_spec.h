@@ -1,0 +1,149 @@
+/* moe_spec -- decode-time Mixture-of-Experts layer step with speculative expert prefetch,
+ * for one AMD MI355X (gfx950).  C ABI: plain pointers and sizes only.
+ *
+ * What one layer step computes (paper: Sec. 3.1-3.3 for the signals, Sec. 4 for the execution
+ * policy, Algorithm 1 and the "Implementation Details" of Sec. 5.1 for the block and its ordering):
+ *
+ *   s_l = LN_l(r_l);  (E_l, G_l) = TopK(Gate_l(s_l))               true routing of layer l
+ *   d_l = sum_{e in E_l} g_{l,e} d_{l,e};  q_l = LN_{l+1}(r_l + d_l)  quasi-hidden state
+ *   (E^_{l+1}, G^_{l+1}) = TopK(Gate_{l+1}(q_l))                    prediction for layer l+1
+ *   prefetch of E^_{l+1} from the pinned host pool into layer l+1's device slots (copy stream)
+ *   O_l = sum_{e in X_l} g_e * W_down_e( silu(W_gate_e s_l) * (W_up_e s_l) )
+ *
+ * X_l (executed experts and their mixing weights) is the set predicted at layer l-1 in
+ * speculative mode (layer 0 of a token is a cold start: true routing, blocking load), and the
+ * true routing in on-demand mode, where the load of E_l blocks the expert computation.
+ * LN is RMSNorm with gain; TopK breaks ties towards the lower expert index; the mixing weights
+ * are a softmax over the k selected logits.  Norms, router logits, top-k and gates are evaluated
+ * in double precision; expert products accumulate in float.  With bf16 weights, s_l, q_l and the
+ * SwiGLU product are rounded to bf16 (nearest even) before they enter a matrix product.
+ *
+ * Memory: "dev" pointers are device memory, "host" pointers are host memory.  The library never
+ * allocates device memory: the caller hands it an arena (see moe_spec_arena_bytes).  The host
+ * expert pool, the resident tables, the arena and both streams are borrowed and must outlive the
+ * context.  The library owns the context, its events and a small pinned mailbox through which
+ * the routing kernels hand expert ids to the host.
+ *
+ * Every call returns a status; nothing throws or aborts; outputs are untouched on error and
+ * moe_spec_last_error gives the reason.  Calls on one context are not thread-safe.
+ */
+#ifndef MOE_SPEC_H
+#define MOE_SPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct moe_spec_ctx moe_spec_ctx;   /* opaque, library-owned */
+
+enum { MOE_SPEC_OK = 0, MOE_SPEC_EINVAL = -1, MOE_SPEC_ENOMEM = -2, MOE_SPEC_ESTATE = -3,
+       MOE_SPEC_EHIP = -4 };
+enum { MOE_SPEC_MODE_ON_DEMAND = 0, MOE_SPEC_MODE_SPECULATIVE = 1 };
+enum { MOE_SPEC_F32 = 0, MOE_SPEC_BF16 = 1 };   /* storage type of every weight table */
+
+/* limits checked by moe_spec_create */
+#define MOE_SPEC_MAX_EXPERTS 256
+#define MOE_SPEC_MAX_TOP_K   16
+#define MOE_SPEC_MAX_BATCH   64
+#define MOE_SPEC_MAX_HIDDEN  8192
+
+typedef struct {
+  int32_t n_layers, hidden, n_experts, top_k, inter;   /* L, H, E, k, I; H and I multiples of 8 */
+  int32_t max_batch;                /* largest decode batch B a step may be called with */
+  int32_t slots_per_layer;          /* S >= k: device cache slots per layer (the memory cap) */
+  int32_t dtype;                    /* MOE_SPEC_F32 | MOE_SPEC_BF16 */
+  int32_t mode;                     /* MOE_SPEC_MODE_* */
+  float   rms_eps;                  /* added to the mean square under the root */
+  int32_t q_from_normalized;        /* 0: q_l = LN_{l+1}(r_l + d_l) (Sec. 3.2 equation);
+                                       1: LN_{l+1}(s_l + d_l) (reading of the caption of Fig. 1) */
+  int32_t predict_in_on_demand;     /* on-demand mode only: 1 still runs the prediction so that
+                                       hit statistics exist; 0 skips it (timing runs) */
+  int32_t profile;                  /* 1: bracket copies and kernels with timing events and fill
+                                       copy_ms / compute_ms / stall_ms (adds a sync per token) */
+  int32_t reserved0;
+  void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
+  size_t  device_arena_bytes;
+  void   *compute_stream;           /* hipStream_t, borrowed; kernels run here */
+  void   *copy_stream;              /* hipStream_t, borrowed; host-to-device expert copies run here */
+} moe_spec_config;
+
+typedef struct {
+  int64_t tokens, layer_steps;
+  int64_t predictions, hits;        /* recall@k of Sec. 3.3: hits = sum |E^_l & E_l|, predictions = sum k */
+  int64_t cache_hits, cache_misses; /* per requested expert */
+  int64_t h2d_bytes;                /* cache_misses * bytes per expert */
+  int64_t hbm_bytes_algorithmic;    /* weight bytes the kernels had to read: routers, default-vector
+                                       rows, executed experts */
+  double  copy_ms, compute_ms, stall_ms;   /* profile=1 only, else 0: copy-stream busy time, kernel
+                                       time, time the compute stream spent waiting for a copy */
+  double  wall_ms;                  /* host clock from the first begin_token after create/reset to
+                                       the end of this call's synchronisation */
+} moe_spec_stats_t;
+
+/* Optional per-step outputs, each dev [B, k] or NULL.  ids are by descending logit. */
+typedef struct {
+  int32_t *true_ids;  float *true_gates;     /* (E_l, G_l) */
+  int32_t *exec_ids;  float *exec_gates;     /* what the expert kernels executed at this layer */
+  int32_t *next_ids;  float *next_gates;     /* (E^_{l+1}, G^_{l+1}); untouched when no prediction ran */
+} moe_spec_step_outputs;
+
+/* Bytes of device arena a context with this configuration needs (slot cache of
+ * L*S expert blocks plus scratch).  Returns 0 if the configuration is invalid. */
+size_t moe_spec_arena_bytes(const moe_spec_config *cfg);
+
+/* Bytes of one expert block in the host pool and in a device slot:
+ * W_gate [I,H] | W_up [I,H] | W_down [H,I], row-major, in the configured dtype. */
+size_t moe_spec_expert_bytes(const moe_spec_config *cfg);
+
+/* Validates cfg (MOE_SPEC_EINVAL), then sets up events and the pinned mailbox on the current
+ * device (MOE_SPEC_EHIP if no usable GPU).  *out is written only on success. */
+int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out);
+
+/* Tables that stay on the device (Sec. 5.1: only experts are offloaded).  router_w dev [E,H] and
+ * default_vecs dev [E,H] in the configured dtype, rms_gain dev [H] float.  Borrowed. */
+int moe_spec_set_layer_resident(moe_spec_ctx *ctx, int layer, const void *router_w,
+                                const void *rms_gain, const void *default_vecs);
+
+/* Registers n_experts consecutive expert blocks of `layer`, starting at first_expert, that live at
+ * pinned_host (host, page-locked: MOE_SPEC_EINVAL otherwise).  bytes must equal
+ * n_experts * moe_spec_expert_bytes.  Nothing is copied: the pool is read at prefetch time. */
+int moe_spec_load_host_experts(moe_spec_ctx *ctx, int layer, int first_expert, int n_experts,
+                               const void *pinned_host, size_t bytes);
+
+/* Starts a decode step: drops the carried prediction, so layer 0 is a cold start (Algorithm 1). */
+int moe_spec_begin_token(moe_spec_ctx *ctx);
+
+/* One MoE block.  r_dev [batch,H] float (post-attention residual r_l), out_dev [batch,H] float
+ * (O_l, valid in compute-stream order).  Layers must be stepped 0,1,...,L-1 after begin_token with
+ * the same batch (MOE_SPEC_ESTATE otherwise, also when a layer's tables or experts were never
+ * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host. */
+int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
+                        const moe_spec_step_outputs *outs);
+
+/* Synchronises both streams, then copies the counters. */
+int moe_spec_stats(moe_spec_ctx *ctx, moe_spec_stats_t *out);
+
+/* Empties the slot cache, drops the carried prediction and zeroes the statistics. */
+int moe_spec_reset(moe_spec_ctx *ctx);
+
+void moe_spec_destroy(moe_spec_ctx *ctx);
+
+/* Text of the last error on this context (or of the last failed moe_spec_create when ctx is NULL). */
+const char *moe_spec_last_error(const moe_spec_ctx *ctx);
+
+/* Measurement aid: launches one of the weight-streaming kernels `reps` times back to back on the
+ * compute stream between two timing events, each launch on the slots of the next layer in turn
+ * (so that no launch finds its weights in a cache), executing k resident slots per launch for a
+ * batch of one.  which: 0 = gate/up GEMV + SwiGLU, 1 = down GEMV, 2 = router (true routing).
+ * Writes the mean milliseconds per launch and the weight bytes one launch reads.
+ * The slot contents are whatever the cache holds; outputs go to scratch. */
+int moe_spec_time_kernel(moe_spec_ctx *ctx, int which, int reps, double *ms_per_launch,
+                         int64_t *bytes_per_launch);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_SPEC_H */

@@ -1,0 +1,289 @@
+// Expert kernels: SwiGLU expert GEMVs gathered over the device cache slots of one layer, and
+// the gate-weighted combine (paper: Algorithm 1, O <- MoE_l(X, ids, g, C_l); Sec. 4 for which ids
+// and gates are executed).
+//
+// A launch covers the experts of one cache wave.  blockIdx.y picks the expert, blockIdx.x a
+// block of output rows.  Each workgroup finds the tokens routed to its expert by scanning the
+// [B,k] id table, stages their activation vectors in LDS, and each wavefront streams whole
+// weight rows with 16-byte loads per lane, reducing across the 64 lanes with shuffles.
+// Weights are read once per token tile; at batch 1 that is exactly once.
+#include "kernels.h"
+
+namespace moe_spec {
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);
+  return v;
+}
+
+// float -> nearest bfloat16 (ties to even) -> float; finite inputs.
+__device__ __forceinline__ float round_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xffff0000u);
+}
+
+template <typename WT> struct Chunk;
+template <> struct Chunk<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static void load(const uint16_t *p, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4 *>(p);
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int N = 4;
+  __device__ static void load(const float *p, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+};
+
+// Positions f = b*k + j of the id table that name expert e, in ascending order, by wavefront 0.
+__device__ __forceinline__ void gather_tokens(const int32_t *ids, int n_ids, int e, int *list,
+                                              int *n_list, int tid) {
+  if (tid < kWave) {
+    int count = 0;
+    for (int base = 0; base < n_ids; base += kWave) {
+      const int f = base + tid;
+      const bool match = f < n_ids && ids[f] == e;
+      const unsigned long long mask = __ballot(match);
+      if (match) list[count + __popcll(mask & ((1ull << tid) - 1ull))] = f;
+      count += __popcll(mask);
+    }
+    if (tid == 0) *n_list = count;
+  }
+  __syncthreads();
+}
+
+// h[f, row] = silu(W_gate[row,:] . s_b) * (W_up[row,:] . s_b) for every position f routed to the expert.
+template <typename WT, int TT>
+__global__ __launch_bounds__(kBlock) void gateup_kernel(const ExpertArgs a, const ActiveList act,
+                                                        const int rpw) {
+  extern __shared__ float act_rows[];          // [TT][H]
+  __shared__ int list[kMaxBatch];
+  __shared__ int n_list;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int H = a.H, I = a.I;
+  constexpr int VN = Chunk<WT>::N;
+
+  const int e = act.expert[blockIdx.y];
+  const WT *wg = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
+  const WT *wu = wg + size_t(I) * H;
+  gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
+  const int n = n_list;
+  const int row0 = (blockIdx.x * kWaves + wave) * rpw;
+
+  for (int t0 = 0; t0 < n; t0 += TT) {
+    const int nt = min(TT, n - t0);
+    for (int t = 0; t < nt; ++t) {
+      const float *src = a.s + size_t(list[t0 + t] / a.k) * H;
+      for (int i = tid * 4; i < H; i += kBlock * 4)
+        *reinterpret_cast<float4 *>(act_rows + size_t(t) * H + i) = *reinterpret_cast<const float4 *>(src + i);
+    }
+    __syncthreads();
+    for (int rr = 0; rr < rpw; ++rr) {
+      const int row = row0 + rr;
+      if (row >= I) break;
+      float ag[TT], au[TT];
+#pragma unroll
+      for (int t = 0; t < TT; ++t) { ag[t] = 0.f; au[t] = 0.f; }
+      const WT *pg = wg + size_t(row) * H;
+      const WT *pu = wu + size_t(row) * H;
+#pragma unroll 4
+      for (int c = lane * VN; c < H; c += kWave * VN) {
+        float fg[VN], fu[VN];
+        Chunk<WT>::load(pg + c, fg);
+        Chunk<WT>::load(pu + c, fu);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+          if (t < nt) {
+            const float *sv = act_rows + size_t(t) * H + c;
+#pragma unroll
+            for (int x = 0; x < VN; ++x) { ag[t] += fg[x] * sv[x]; au[t] += fu[x] * sv[x]; }
+          }
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < TT; ++t) {
+        if (t < nt) {
+          const float g = wave_sum(ag[t]);
+          const float u = wave_sum(au[t]);
+          if (lane == 0) {
+            float hv = g / (1.f + expf(-g)) * u;
+            if (a.bf16) hv = round_to_bf16(hv);
+            a.h[size_t(list[t0 + t]) * I + row] = hv;
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// y[f, row] = W_down[row,:] . h[f,:] for every position f routed to the expert.
+template <typename WT, int TT>
+__global__ __launch_bounds__(kBlock) void down_kernel(const ExpertArgs a, const ActiveList act,
+                                                      const int rpw) {
+  extern __shared__ float act_rows[];          // [TT][I]
+  __shared__ int list[kMaxBatch];
+  __shared__ int n_list;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int H = a.H, I = a.I;
+  constexpr int VN = Chunk<WT>::N;
+
+  const int e = act.expert[blockIdx.y];
+  const WT *wd = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes) +
+                 size_t(2) * I * H;
+  gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
+  const int n = n_list;
+  const int row0 = (blockIdx.x * kWaves + wave) * rpw;
+
+  for (int t0 = 0; t0 < n; t0 += TT) {
+    const int nt = min(TT, n - t0);
+    for (int t = 0; t < nt; ++t) {
+      const float *src = a.h + size_t(list[t0 + t]) * I;
+      for (int i = tid * 4; i < I; i += kBlock * 4)
+        *reinterpret_cast<float4 *>(act_rows + size_t(t) * I + i) = *reinterpret_cast<const float4 *>(src + i);
+    }
+    __syncthreads();
+    for (int rr = 0; rr < rpw; ++rr) {
+      const int row = row0 + rr;
+      if (row >= H) break;
+      float acc[TT];
+#pragma unroll
+      for (int t = 0; t < TT; ++t) acc[t] = 0.f;
+      const WT *pw = wd + size_t(row) * I;
+#pragma unroll 4
+      for (int c = lane * VN; c < I; c += kWave * VN) {
+        float fw[VN];
+        Chunk<WT>::load(pw + c, fw);
+#pragma unroll
+        for (int t = 0; t < TT; ++t) {
+          if (t < nt) {
+            const float *hv = act_rows + size_t(t) * I + c;
+#pragma unroll
+            for (int x = 0; x < VN; ++x) acc[t] += fw[x] * hv[x];
+          }
+        }
+      }
+#pragma unroll
+      for (int t = 0; t < TT; ++t) {
+        if (t < nt) {
+          const float v = wave_sum(acc[t]);
+          if (lane == 0) a.y[size_t(list[t0 + t]) * H + row] = v;
+        }
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// O[b, i] = sum_j gates[b, j] * y[b, j, i]
+__global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  const int b = blockIdx.y;
+  if (i >= a.H) return;
+  float acc = 0.f;
+  for (int j = 0; j < a.k; ++j)
+    acc += a.exec_gates[b * a.k + j] * a.y[(size_t(b) * a.k + j) * a.H + i];
+  a.out[size_t(b) * a.H + i] = acc;
+}
+
+int pick_tok_tile(int B, int row_len) {
+  int tt = 1;
+  while (tt < B && tt < 8) tt <<= 1;
+  while (tt > 1 && size_t(tt) * row_len * sizeof(float) > (size_t(60) << 10)) tt >>= 1;
+  return tt;
+}
+
+int pick_rows_per_wave(int rows, int n_active) {
+  // aim for about 2048 workgroups so that all 256 compute units hold several
+  const long total = long(rows) * n_active;
+  long rpw = total / (long(kWaves) * 2048);
+  if (rpw < 1) rpw = 1;
+  if (rpw > 8) rpw = 8;
+  return int(rpw);
+}
+
+template <typename WT>
+hipError_t launch_gateup_t(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  const int tt = pick_tok_tile(a.B, a.H);
+  const int rpw = pick_rows_per_wave(a.I, act.n);
+  const size_t lds = size_t(tt) * a.H * sizeof(float);
+  const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
+  switch (tt) {
+    case 1: hipLaunchKernelGGL((gateup_kernel<WT, 1>), grid, block, lds, st, a, act, rpw); break;
+    case 2: hipLaunchKernelGGL((gateup_kernel<WT, 2>), grid, block, lds, st, a, act, rpw); break;
+    case 4: hipLaunchKernelGGL((gateup_kernel<WT, 4>), grid, block, lds, st, a, act, rpw); break;
+    default: hipLaunchKernelGGL((gateup_kernel<WT, 8>), grid, block, lds, st, a, act, rpw); break;
+  }
+  return hipGetLastError();
+}
+
+template <typename WT>
+hipError_t launch_down_t(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  const int tt = pick_tok_tile(a.B, a.I);
+  const int rpw = pick_rows_per_wave(a.H, act.n);
+  const size_t lds = size_t(tt) * a.I * sizeof(float);
+  const dim3 grid((a.H + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
+  switch (tt) {
+    case 1: hipLaunchKernelGGL((down_kernel<WT, 1>), grid, block, lds, st, a, act, rpw); break;
+    case 2: hipLaunchKernelGGL((down_kernel<WT, 2>), grid, block, lds, st, a, act, rpw); break;
+    case 4: hipLaunchKernelGGL((down_kernel<WT, 4>), grid, block, lds, st, a, act, rpw); break;
+    default: hipLaunchKernelGGL((down_kernel<WT, 8>), grid, block, lds, st, a, act, rpw); break;
+  }
+  return hipGetLastError();
+}
+
+template <typename K>
+hipError_t allow_big_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 128 << 10);
+}
+
+}  // namespace
+
+hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
+  if (act.n <= 0) return hipSuccess;
+  return dtype == 1 ? launch_gateup_t<uint16_t>(a, act, st) : launch_gateup_t<float>(a, act, st);
+}
+
+hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
+  if (act.n <= 0) return hipSuccess;
+  return dtype == 1 ? launch_down_t<uint16_t>(a, act, st) : launch_down_t<float>(a, act, st);
+}
+
+hipError_t launch_combine(const ExpertArgs &a, hipStream_t st) {
+  const dim3 grid((a.H + kBlock - 1) / kBlock, a.B), block(kBlock);
+  hipLaunchKernelGGL(combine_kernel, grid, block, 0, st, a);
+  return hipGetLastError();
+}
+
+hipError_t init_route_kernels();
+
+hipError_t init_kernels() {
+  hipError_t e = init_route_kernels();
+#define MOE_SPEC_ALLOW(k) if (e == hipSuccess) e = allow_big_lds(k)
+  MOE_SPEC_ALLOW((gateup_kernel<uint16_t, 1>)); MOE_SPEC_ALLOW((gateup_kernel<uint16_t, 2>));
+  MOE_SPEC_ALLOW((gateup_kernel<uint16_t, 4>)); MOE_SPEC_ALLOW((gateup_kernel<uint16_t, 8>));
+  MOE_SPEC_ALLOW((gateup_kernel<float, 1>)); MOE_SPEC_ALLOW((gateup_kernel<float, 2>));
+  MOE_SPEC_ALLOW((gateup_kernel<float, 4>)); MOE_SPEC_ALLOW((gateup_kernel<float, 8>));
+  MOE_SPEC_ALLOW((down_kernel<uint16_t, 1>)); MOE_SPEC_ALLOW((down_kernel<uint16_t, 2>));
+  MOE_SPEC_ALLOW((down_kernel<uint16_t, 4>)); MOE_SPEC_ALLOW((down_kernel<uint16_t, 8>));
+  MOE_SPEC_ALLOW((down_kernel<float, 1>)); MOE_SPEC_ALLOW((down_kernel<float, 2>));
+  MOE_SPEC_ALLOW((down_kernel<float, 4>)); MOE_SPEC_ALLOW((down_kernel<float, 8>));
+#undef MOE_SPEC_ALLOW
+  return e;
+}
+
+}  // namespace moe_spec

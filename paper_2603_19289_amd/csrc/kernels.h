@@ -1,0 +1,78 @@
+// Argument blocks and launchers of the device kernels.  Host code sees only this header.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe_spec {
+
+constexpr int kMaxExperts = 256;
+constexpr int kMaxTopK = 16;
+constexpr int kMaxBatch = 64;
+constexpr int kRouteBlock = 256;        // threads per workgroup of the routing kernels
+constexpr int kRouteRowsPerBlock = 4;   // one router row per wavefront
+constexpr int kMailboxIds = kMaxBatch * kMaxTopK;
+
+// Pinned host mailbox written by the last workgroup of a routing kernel.
+struct Mailbox {
+  int32_t ids[kMailboxIds];   // [B, k] expert ids by descending logit
+  uint32_t seq;               // written last; the host spins until it equals the step's ticket
+  uint32_t pad[15];
+};
+
+// Routing kernel: RMSNorm -> router GEMV -> top-k -> softmax over the selected logits.
+// spec = 0: input is r_l (true routing of layer l).
+// spec = 1: input is r_l (or s_l) + sum_j g_j d_{l,e_j}, normalised with layer l+1's gain and
+//           routed with layer l+1's router (the quasi-hidden state of Sec. 3.2).
+struct RouteArgs {
+  const float *r;             // [B,H]
+  const float *s_in;          // [B,H] s_l, read when spec && from_normalized
+  const void *w;              // [E,H] router weights of the layer being routed
+  const float *gain;          // [H] gain of that layer's norm
+  const void *dvec;           // spec: [E,H] default vectors of layer l
+  const int32_t *d_ids;       // spec: [B,k] true ids of layer l
+  const double *d_gates;      // spec: [B,k] true gates of layer l
+  double *z;                  // [B,E] logits scratch
+  unsigned int *counter;      // arrival counter, zero between launches
+  float *vec_out;             // [B,H] normalised (and rounded) vector, or null
+  int32_t *ids_out;           // [B,k]
+  float *gates_out;           // [B,k]
+  double *gates64_out;        // [B,k] or null
+  const int32_t *cmp_ids;     // [B,k] prediction to score against this routing, or null
+  unsigned long long *hit_counters;   // [2] hits, predictions
+  int32_t *user_ids;          // optional copies for the caller
+  float *user_gates;
+  Mailbox *mailbox;           // pinned host, or null
+  uint32_t seq;
+  int B, H, E, k;
+  float eps;
+  int bf16, spec, from_normalized, tok_tile;
+};
+
+// Expert kernels read weights from the device slots of one layer.
+struct ActiveList {           // experts executed by one launch and where they live
+  int32_t n;
+  int16_t expert[kMaxExperts];
+  int16_t slot[kMaxExperts];
+};
+
+struct ExpertArgs {
+  const char *pool;           // first slot of the layer's pool
+  size_t slot_bytes;          // distance between slots (expert block bytes)
+  const float *s;             // [B,H] router input s_l
+  const int32_t *exec_ids;    // [B,k]
+  const float *exec_gates;    // [B,k]
+  float *h;                   // [B,k,I] SwiGLU products
+  float *y;                   // [B,k,H] un-gated expert outputs
+  float *out;                 // [B,H]
+  int B, k, H, I, bf16, tok_tile;
+};
+
+hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
+hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
+hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
+hipError_t launch_combine(const ExpertArgs &a, hipStream_t st);
+hipError_t init_kernels();     // one-time function attributes (dynamic LDS limits)
+
+size_t route_lds_bytes(int H, int B, int *tok_tile);
+
+}  // namespace moe_spec

@@ -1,0 +1,672 @@
+// Host side of the library: context, slot cache, stream/event ordering, C ABI.
+//
+// Ordering of one layer step (paper: Algorithm 1 and the wait-and-prefetch description in
+// Sec. 5.1 "Implementation Details"; here with per-layer slot pools instead of two buffers):
+//   compute stream: route(l) -> predict(l+1) -> [wait ready(l)] -> gate/up -> down -> combine
+//   copy stream   : [wait done(l+1) of the previous token] -> H2D of the missing experts of
+//                   layer l+1 -> record ready(l+1)
+// The host learns expert ids through a pinned mailbox the routing kernels write; it needs them
+// to decide which slots to fill.  done(l) is recorded after the last kernel that reads pool l, and
+// every copy into pool l waits for it, so a slot is never overwritten while it is being read.
+#include "../../include/moe_spec.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace moe_spec;
+
+namespace {
+
+thread_local std::string g_create_error;
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Pool {                       // one layer's slot cache (least recently used replacement)
+  std::vector<int> slot_expert, slot_stamp, where;   // where[e] = slot or -1
+  long clock = 0;
+};
+
+struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall
+
+struct ArenaLayout {
+  size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
+      hit_counters, h, y, bench_ids, total;
+};
+
+const char *validate(const moe_spec_config *c) {
+  if (!c) return "config is null";
+  if (c->n_layers < 1) return "n_layers must be >= 1";
+  if (c->hidden < 8 || c->hidden % 8) return "hidden must be a positive multiple of 8";
+  if (c->hidden > MOE_SPEC_MAX_HIDDEN) return "hidden exceeds MOE_SPEC_MAX_HIDDEN";
+  if (c->inter < 8 || c->inter % 8) return "inter must be a positive multiple of 8";
+  if (c->inter > 32768) return "inter exceeds 32768";
+  if (c->n_experts < 1 || c->n_experts > MOE_SPEC_MAX_EXPERTS) return "n_experts out of range";
+  if (c->top_k < 1 || c->top_k > MOE_SPEC_MAX_TOP_K || c->top_k > c->n_experts) return "top_k out of range";
+  if (c->max_batch < 1 || c->max_batch > MOE_SPEC_MAX_BATCH) return "max_batch out of range";
+  if (c->slots_per_layer < c->top_k) return "slots_per_layer must be at least top_k";
+  if (c->slots_per_layer > 32767) return "slots_per_layer too large";
+  if (c->dtype != MOE_SPEC_F32 && c->dtype != MOE_SPEC_BF16) return "unknown dtype";
+  if (c->mode != MOE_SPEC_MODE_ON_DEMAND && c->mode != MOE_SPEC_MODE_SPECULATIVE) return "unknown mode";
+  if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
+  return nullptr;
+}
+
+size_t expert_bytes_of(const moe_spec_config *c) {
+  return size_t(3) * c->hidden * c->inter * (c->dtype == MOE_SPEC_BF16 ? 2 : 4);
+}
+
+ArenaLayout layout_of(const moe_spec_config *c) {
+  ArenaLayout a{};
+  const size_t B = c->max_batch, k = c->top_k, H = c->hidden, I = c->inter, E = c->n_experts;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+  a.slots = take(size_t(c->n_layers) * c->slots_per_layer * align_up(expert_bytes_of(c), 256));
+  a.s_buf = take(B * H * 4);
+  a.z = take(B * E * 8);
+  a.counter = take(256);
+  a.true_ids = take(B * k * 4);
+  a.true_gates = take(B * k * 4);
+  a.true_gates64 = take(B * k * 8);
+  for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
+  a.hit_counters = take(256);
+  a.h = take(B * k * I * 4);
+  a.y = take(B * k * H * 4);
+  a.bench_ids = take(256);
+  a.total = off;
+  return a;
+}
+
+}  // namespace
+
+struct moe_spec_ctx {
+  moe_spec_config cfg{};
+  size_t expert_bytes = 0, slot_stride = 0;
+  ArenaLayout lay{};
+  char *arena = nullptr;
+  hipStream_t compute = nullptr, copy = nullptr;
+
+  std::vector<const void *> router_w, gain, dvecs;
+  std::vector<const char *> host_expert;        // [L*E]
+  std::vector<Pool> pools;
+  std::vector<hipEvent_t> ready, done;
+  std::vector<char> done_recorded;
+  Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
+  Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
+  uint32_t seq = 0;
+
+  // token state
+  bool token_open = false;
+  int next_layer = 0, batch = 0;
+  bool have_pending = false;                    // a prediction for next_layer sits on the device
+  std::vector<int> pending_union;               // sorted union of predicted ids (host copy)
+  ActiveList pending_wave0{};                   // slots of its first wave (already requested)
+
+  // statistics
+  moe_spec_stats_t st{};
+  bool clock_running = false;
+  std::chrono::steady_clock::time_point t0;
+  std::deque<TimedSpan> spans;     // addresses stay valid while a span is open
+  std::vector<hipEvent_t> free_events;
+
+  std::string err;
+
+  int fail(int code, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    err = buf;
+    return code;
+  }
+  int hip_fail(hipError_t e, const char *what) {
+    return fail(MOE_SPEC_EHIP, "%s: %s", what, hipGetErrorString(e));
+  }
+
+  template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(arena + off); }
+  char *pool_base(int layer) const {
+    return arena + lay.slots + size_t(layer) * cfg.slots_per_layer * slot_stride;
+  }
+
+  hipEvent_t timing_event() {
+    if (!free_events.empty()) { hipEvent_t e = free_events.back(); free_events.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  // record (a) now, return span whose (b) the caller records later
+  TimedSpan *open_span(int kind, hipStream_t s) {
+    if (!cfg.profile) return nullptr;
+    TimedSpan sp{timing_event(), timing_event(), kind};
+    if (!sp.a || !sp.b) return nullptr;
+    (void)hipEventRecord(sp.a, s);
+    spans.push_back(sp);
+    return &spans.back();
+  }
+  void close_span(TimedSpan *sp, hipStream_t s) { if (sp) (void)hipEventRecord(sp->b, s); }
+  int resolve_spans() {
+    if (spans.empty()) return MOE_SPEC_OK;
+    hipError_t e = hipStreamSynchronize(compute);
+    if (e == hipSuccess) e = hipStreamSynchronize(copy);
+    if (e != hipSuccess) return hip_fail(e, "synchronize for timing");
+    for (auto &sp : spans) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) {
+        if (sp.kind == 0) st.compute_ms += ms; else if (sp.kind == 1) st.copy_ms += ms; else st.stall_ms += ms;
+      }
+      free_events.push_back(sp.a);
+      free_events.push_back(sp.b);
+    }
+    spans.clear();
+    return MOE_SPEC_OK;
+  }
+
+  // Spin until the mailbox shows this ticket.  Bounded; also notices a failed stream.
+  int wait_mailbox(const Mailbox *mb, uint32_t ticket) {
+    const volatile uint32_t *flag = &mb->seq;
+    auto start = std::chrono::steady_clock::now();
+    unsigned long spins = 0;
+    while (*flag != ticket) {
+      __builtin_ia32_pause();
+      if ((++spins & 0xfffff) == 0) {
+        hipError_t q = hipStreamQuery(compute);
+        if (q != hipSuccess && q != hipErrorNotReady) return hip_fail(q, "compute stream failed while routing");
+        if (q == hipSuccess && *flag != ticket)
+          return fail(MOE_SPEC_EHIP, "routing kernel finished without posting expert ids");
+        if (std::chrono::steady_clock::now() - start > std::chrono::seconds(30))
+          return fail(MOE_SPEC_EHIP, "timed out waiting for expert ids from the routing kernel");
+      }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return MOE_SPEC_OK;
+  }
+
+  // Cache request for at most S experts (ascending ids): hits are stamped, each miss takes the
+  // least recently used slot that holds no requested expert and is copied in on the copy stream.
+  // Fills act with (expert, slot) of every requested expert.  Returns the number of copies issued.
+  int request(int layer, const std::vector<int> &experts, ActiveList *act, int *n_copies) {
+    Pool &p = pools[layer];
+    const int S = cfg.slots_per_layer;
+    p.clock += 1;
+    std::vector<char> in_q(cfg.n_experts, 0);
+    for (int e : experts) in_q[e] = 1;
+    act->n = 0;
+    int copies = 0;
+    TimedSpan *span = nullptr;
+    for (int e : experts) {
+      if (p.where[e] >= 0) { p.slot_stamp[p.where[e]] = int(p.clock); st.cache_hits += 1; }
+    }
+    for (int e : experts) {
+      if (p.where[e] >= 0) continue;
+      int victim = -1;
+      for (int s = 0; s < S; ++s) {
+        const int held = p.slot_expert[s];
+        if (held >= 0 && in_q[held]) continue;
+        if (victim < 0 || p.slot_stamp[s] < p.slot_stamp[victim]) victim = s;
+      }
+      if (victim < 0) return fail(MOE_SPEC_ESTATE, "no evictable slot (request larger than the pool)");
+      const char *src = host_expert[size_t(layer) * cfg.n_experts + e];
+      if (!src) return fail(MOE_SPEC_ESTATE, "expert %d of layer %d was never registered", e, layer);
+      if (copies == 0) {
+        if (done_recorded[layer]) {
+          hipError_t w = hipStreamWaitEvent(copy, done[layer], 0);
+          if (w != hipSuccess) return hip_fail(w, "copy stream wait");
+        }
+        span = open_span(1, copy);
+      }
+      if (p.slot_expert[victim] >= 0) p.where[p.slot_expert[victim]] = -1;
+      p.slot_expert[victim] = e;
+      p.slot_stamp[victim] = int(p.clock);
+      p.where[e] = victim;
+      hipError_t c = hipMemcpyAsync(pool_base(layer) + size_t(victim) * slot_stride, src, expert_bytes,
+                                    hipMemcpyHostToDevice, copy);
+      if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
+      copies += 1;
+      st.cache_misses += 1;
+      st.h2d_bytes += int64_t(expert_bytes);
+    }
+    if (copies > 0) {
+      close_span(span, copy);
+      hipError_t r = hipEventRecord(ready[layer], copy);
+      if (r != hipSuccess) return hip_fail(r, "record ready event");
+    }
+    for (int e : experts) {
+      act->expert[act->n] = int16_t(e);
+      act->slot[act->n] = int16_t(p.where[e]);
+      act->n += 1;
+    }
+    *n_copies = copies;
+    return MOE_SPEC_OK;
+  }
+
+  static std::vector<int> sorted_union(const int32_t *ids, int n) {
+    std::vector<int> u(ids, ids + n);
+    std::sort(u.begin(), u.end());
+    u.erase(std::unique(u.begin(), u.end()), u.end());
+    return u;
+  }
+};
+
+extern "C" {
+
+size_t moe_spec_expert_bytes(const moe_spec_config *cfg) {
+  if (validate(cfg)) return 0;
+  return expert_bytes_of(cfg);
+}
+
+size_t moe_spec_arena_bytes(const moe_spec_config *cfg) {
+  if (validate(cfg)) return 0;
+  return layout_of(cfg).total;
+}
+
+const char *moe_spec_last_error(const moe_spec_ctx *ctx) {
+  return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
+  if (!out) { g_create_error = "out is null"; return MOE_SPEC_EINVAL; }
+  if (const char *why = validate(cfg)) { g_create_error = why; return MOE_SPEC_EINVAL; }
+  const ArenaLayout lay = layout_of(cfg);
+  if (!cfg->device_arena || (reinterpret_cast<uintptr_t>(cfg->device_arena) & 255)) {
+    g_create_error = "device_arena must be a 256-byte aligned device pointer";
+    return MOE_SPEC_EINVAL;
+  }
+  if (cfg->device_arena_bytes < lay.total) {
+    g_create_error = "device_arena_bytes is smaller than moe_spec_arena_bytes(cfg)";
+    return MOE_SPEC_EINVAL;
+  }
+  int n_dev = 0;
+  hipError_t e = hipGetDeviceCount(&n_dev);
+  if (e != hipSuccess || n_dev < 1) {
+    g_create_error = std::string("no usable GPU: ") + (e != hipSuccess ? hipGetErrorString(e) : "device count is 0");
+    return MOE_SPEC_EHIP;
+  }
+  moe_spec_ctx *c = new (std::nothrow) moe_spec_ctx;
+  if (!c) { g_create_error = "out of host memory"; return MOE_SPEC_ENOMEM; }
+  c->cfg = *cfg;
+  c->lay = lay;
+  c->expert_bytes = expert_bytes_of(cfg);
+  c->slot_stride = align_up(c->expert_bytes, 256);
+  c->arena = static_cast<char *>(cfg->device_arena);
+  c->compute = static_cast<hipStream_t>(cfg->compute_stream);
+  c->copy = static_cast<hipStream_t>(cfg->copy_stream);
+  const int L = cfg->n_layers, E = cfg->n_experts, S = cfg->slots_per_layer;
+  c->router_w.assign(L, nullptr);
+  c->gain.assign(L, nullptr);
+  c->dvecs.assign(L, nullptr);
+  c->host_expert.assign(size_t(L) * E, nullptr);
+  c->pools.resize(L);
+  for (auto &p : c->pools) { p.slot_expert.assign(S, -1); p.slot_stamp.assign(S, -1); p.where.assign(E, -1); }
+  c->done_recorded.assign(L, 0);
+
+  auto bail = [&](hipError_t err, const char *what) {
+    g_create_error = std::string(what) + ": " + hipGetErrorString(err);
+    moe_spec_destroy(c);
+    return MOE_SPEC_EHIP;
+  };
+  if ((e = init_kernels()) != hipSuccess) return bail(e, "kernel attributes");
+  c->ready.assign(L, nullptr);
+  c->done.assign(L, nullptr);
+  for (int l = 0; l < L; ++l) {
+    if ((e = hipEventCreateWithFlags(&c->ready[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+    if ((e = hipEventCreateWithFlags(&c->done[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+  }
+  void *mb = nullptr;
+  // fine-grained (coherent) pinned memory: device stores become visible to the spinning host
+  if ((e = hipHostMalloc(&mb, 2 * sizeof(Mailbox), hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+    return bail(e, "pinned mailbox");
+  std::memset(mb, 0, 2 * sizeof(Mailbox));
+  c->mb_true = static_cast<Mailbox *>(mb);
+  c->mb_next = c->mb_true + 1;
+  void *mb_dev = nullptr;
+  if ((e = hipHostGetDevicePointer(&mb_dev, mb, 0)) != hipSuccess) return bail(e, "mailbox device pointer");
+  c->mb_true_dev = static_cast<Mailbox *>(mb_dev);
+  c->mb_next_dev = c->mb_true_dev + 1;
+  // counters start at zero
+  if ((e = hipMemsetAsync(c->arena + lay.counter, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counter");
+  if ((e = hipMemsetAsync(c->arena + lay.hit_counters, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counters");
+  if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return bail(e, "synchronize");
+  *out = c;
+  return MOE_SPEC_OK;
+}
+
+void moe_spec_destroy(moe_spec_ctx *c) {
+  if (!c) return;
+  if (c->compute || c->copy || c->mb_true) {
+    (void)hipStreamSynchronize(c->compute);
+    (void)hipStreamSynchronize(c->copy);
+  }
+  for (auto ev : c->ready) if (ev) (void)hipEventDestroy(ev);
+  for (auto ev : c->done) if (ev) (void)hipEventDestroy(ev);
+  for (auto &sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
+  for (auto ev : c->free_events) (void)hipEventDestroy(ev);
+  if (c->mb_true) (void)hipHostFree(c->mb_true);
+  delete c;
+}
+
+int moe_spec_set_layer_resident(moe_spec_ctx *c, int layer, const void *router_w, const void *rms_gain,
+                                const void *default_vecs) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
+  if (!router_w || !rms_gain || !default_vecs) return c->fail(MOE_SPEC_EINVAL, "null table pointer");
+  if ((reinterpret_cast<uintptr_t>(router_w) | reinterpret_cast<uintptr_t>(default_vecs)) & 15)
+    return c->fail(MOE_SPEC_EINVAL, "tables must be 16-byte aligned");
+  c->router_w[layer] = router_w;
+  c->gain[layer] = rms_gain;
+  c->dvecs[layer] = default_vecs;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_load_host_experts(moe_spec_ctx *c, int layer, int first_expert, int n_experts,
+                               const void *pinned_host, size_t bytes) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (layer < 0 || layer >= c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
+  if (first_expert < 0 || n_experts < 1 || first_expert + n_experts > c->cfg.n_experts)
+    return c->fail(MOE_SPEC_EINVAL, "expert range [%d, %d) out of range", first_expert, first_expert + n_experts);
+  if (!pinned_host) return c->fail(MOE_SPEC_EINVAL, "host pointer is null");
+  if (bytes != size_t(n_experts) * c->expert_bytes)
+    return c->fail(MOE_SPEC_EINVAL, "bytes must be n_experts * %zu", c->expert_bytes);
+  hipPointerAttribute_t attr;
+  hipError_t e = hipPointerGetAttributes(&attr, pinned_host);
+  if (e != hipSuccess || attr.type != hipMemoryTypeHost) {
+    (void)hipGetLastError();
+    return c->fail(MOE_SPEC_EINVAL, "host pool must be page-locked (pinned) host memory");
+  }
+  for (int i = 0; i < n_experts; ++i)
+    c->host_expert[size_t(layer) * c->cfg.n_experts + first_expert + i] =
+        static_cast<const char *>(pinned_host) + size_t(i) * c->expert_bytes;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_begin_token(moe_spec_ctx *c) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (c->cfg.profile) { int rc = c->resolve_spans(); if (rc) return rc; }
+  if (!c->clock_running) { c->clock_running = true; c->t0 = std::chrono::steady_clock::now(); }
+  c->token_open = true;
+  c->next_layer = 0;
+  c->batch = 0;
+  c->have_pending = false;
+  c->pending_union.clear();
+  c->st.tokens += 1;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch, void *out_dev,
+                        const moe_spec_step_outputs *outs) {
+  if (!c) return MOE_SPEC_EINVAL;
+  const moe_spec_config &cfg = c->cfg;
+  if (!r_dev || !out_dev) return c->fail(MOE_SPEC_EINVAL, "null activation pointer");
+  if (batch < 1 || batch > cfg.max_batch) return c->fail(MOE_SPEC_EINVAL, "batch %d out of range", batch);
+  if (!c->token_open) return c->fail(MOE_SPEC_ESTATE, "layer_step before begin_token");
+  if (layer != c->next_layer) return c->fail(MOE_SPEC_ESTATE, "expected layer %d, got %d", c->next_layer, layer);
+  if (layer > 0 && batch != c->batch) return c->fail(MOE_SPEC_ESTATE, "batch changed inside a token");
+  const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter, S = cfg.slots_per_layer;
+  const bool last = layer == L - 1;
+  if (!c->router_w[layer] || (!last && !c->router_w[layer + 1]))
+    return c->fail(MOE_SPEC_ESTATE, "resident tables of layer %d (or %d) were never set", layer, layer + 1);
+  const bool spec_mode = cfg.mode == MOE_SPEC_MODE_SPECULATIVE;
+  const bool do_pred = !last && (spec_mode || cfg.predict_in_on_demand);
+  const bool exec_pred = spec_mode && c->have_pending;
+  const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
+  hipError_t e;
+
+  TimedSpan *sp_route = c->open_span(0, c->compute);
+
+  // --- true routing of layer l (and scoring of the prediction made at l-1)
+  RouteArgs ra{};
+  ra.r = static_cast<const float *>(r_dev);
+  ra.w = c->router_w[layer];
+  ra.gain = static_cast<const float *>(c->gain[layer]);
+  ra.z = c->at<double>(c->lay.z);
+  ra.counter = c->at<unsigned int>(c->lay.counter);
+  ra.vec_out = c->at<float>(c->lay.s_buf);
+  ra.ids_out = c->at<int32_t>(c->lay.true_ids);
+  ra.gates_out = c->at<float>(c->lay.true_gates);
+  ra.gates64_out = c->at<double>(c->lay.true_gates64);
+  ra.cmp_ids = c->have_pending ? c->at<int32_t>(c->lay.pend_ids[layer & 1]) : nullptr;
+  ra.hit_counters = c->at<unsigned long long>(c->lay.hit_counters);
+  ra.user_ids = outs ? outs->true_ids : nullptr;
+  ra.user_gates = outs ? outs->true_gates : nullptr;
+  ra.mailbox = exec_pred ? nullptr : c->mb_true_dev;
+  const uint32_t ticket_true = ++c->seq;
+  ra.seq = ticket_true;
+  ra.B = batch; ra.H = H; ra.E = E; ra.k = k;
+  ra.eps = cfg.rms_eps;
+  ra.bf16 = cfg.dtype == MOE_SPEC_BF16;
+  ra.spec = 0;
+  if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+  c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
+
+  // --- prediction for layer l+1 from the quasi-hidden state
+  uint32_t ticket_next = 0;
+  if (do_pred) {
+    RouteArgs pa = ra;
+    pa.s_in = c->at<float>(c->lay.s_buf);
+    pa.w = c->router_w[layer + 1];
+    pa.gain = static_cast<const float *>(c->gain[layer + 1]);
+    pa.dvec = c->dvecs[layer];
+    pa.d_ids = c->at<int32_t>(c->lay.true_ids);
+    pa.d_gates = c->at<double>(c->lay.true_gates64);
+    pa.vec_out = nullptr;
+    pa.ids_out = c->at<int32_t>(c->lay.pend_ids[(layer + 1) & 1]);
+    pa.gates_out = c->at<float>(c->lay.pend_gates[(layer + 1) & 1]);
+    pa.gates64_out = nullptr;
+    pa.cmp_ids = nullptr;
+    pa.user_ids = outs ? outs->next_ids : nullptr;
+    pa.user_gates = outs ? outs->next_gates : nullptr;
+    pa.mailbox = spec_mode ? c->mb_next_dev : nullptr;
+    ticket_next = ++c->seq;
+    pa.seq = ticket_next;
+    pa.spec = 1;
+    pa.from_normalized = cfg.q_from_normalized;
+    if ((e = launch_route(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "prediction kernel");
+    c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+  }
+  c->close_span(sp_route, c->compute);
+
+  // --- which experts run, and where their ids and gates live on the device
+  std::vector<int> exec_union;
+  const int32_t *exec_ids_dev;
+  const float *exec_gates_dev;
+  if (exec_pred) {
+    exec_union = c->pending_union;
+    exec_ids_dev = c->at<int32_t>(c->lay.pend_ids[layer & 1]);
+    exec_gates_dev = c->at<float>(c->lay.pend_gates[layer & 1]);
+  } else {
+    int rc = c->wait_mailbox(c->mb_true, ticket_true);
+    if (rc) return rc;
+    exec_union = moe_spec_ctx::sorted_union(c->mb_true->ids, batch * k);
+    exec_ids_dev = c->at<int32_t>(c->lay.true_ids);
+    exec_gates_dev = c->at<float>(c->lay.true_gates);
+  }
+  if (outs && outs->exec_ids) {
+    if ((e = hipMemcpyAsync(outs->exec_ids, exec_ids_dev, size_t(batch) * k * 4, hipMemcpyDeviceToDevice, c->compute)) != hipSuccess)
+      return c->hip_fail(e, "copy exec ids");
+  }
+  if (outs && outs->exec_gates) {
+    if ((e = hipMemcpyAsync(outs->exec_gates, exec_gates_dev, size_t(batch) * k * 4, hipMemcpyDeviceToDevice, c->compute)) != hipSuccess)
+      return c->hip_fail(e, "copy exec gates");
+  }
+
+  ExpertArgs xa{};
+  xa.pool = c->pool_base(layer);
+  xa.slot_bytes = c->slot_stride;
+  xa.s = c->at<float>(c->lay.s_buf);
+  xa.exec_ids = exec_ids_dev;
+  xa.exec_gates = exec_gates_dev;
+  xa.h = c->at<float>(c->lay.h);
+  xa.y = c->at<float>(c->lay.y);
+  xa.out = static_cast<float *>(out_dev);
+  xa.B = batch; xa.k = k; xa.H = H; xa.I = I;
+  xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
+
+  // --- cache waves: make resident (unless prefetched), wait, run
+  TimedSpan *sp_stall = c->open_span(2, c->compute);
+  bool stall_open = sp_stall != nullptr;
+  TimedSpan *sp_exec = nullptr;
+  for (size_t w0 = 0, wave = 0; w0 < exec_union.size(); w0 += S, ++wave) {
+    ActiveList act{};
+    int copies = 0;
+    bool need_wait;
+    if (exec_pred && wave == 0) {
+      act = c->pending_wave0;
+      need_wait = true;                         // the prefetch may still be in flight
+    } else {
+      std::vector<int> req(exec_union.begin() + w0, exec_union.begin() + std::min(exec_union.size(), w0 + S));
+      int rc = c->request(layer, req, &act, &copies);
+      if (rc) return rc;
+      need_wait = copies > 0;
+    }
+    if (need_wait && (e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess)
+      return c->hip_fail(e, "compute stream wait");
+    if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
+    if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+    if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+    if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
+    c->done_recorded[layer] = 1;
+    c->st.hbm_bytes_algorithmic += int64_t(act.n) * int64_t(c->expert_bytes);
+  }
+  if ((e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
+  c->close_span(sp_exec, c->compute);
+
+  // --- prefetch the first wave of the predicted experts of layer l+1
+  c->have_pending = do_pred;
+  if (do_pred && spec_mode) {
+    int rc = c->wait_mailbox(c->mb_next, ticket_next);
+    if (rc) return rc;
+    c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
+    std::vector<int> req(c->pending_union.begin(),
+                         c->pending_union.begin() + std::min<size_t>(c->pending_union.size(), S));
+    int copies = 0;
+    rc = c->request(layer + 1, req, &c->pending_wave0, &copies);
+    if (rc) return rc;
+    if (copies == 0) {
+      // nothing to copy: make the wait at the next step a no-op that is still well defined
+      if ((e = hipEventRecord(c->ready[layer + 1], c->copy)) != hipSuccess) return c->hip_fail(e, "record ready event");
+    }
+  }
+
+  c->batch = batch;
+  c->next_layer = layer + 1;
+  if (last) c->token_open = false;
+  c->st.layer_steps += 1;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_stats(moe_spec_ctx *c, moe_spec_stats_t *out) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (!out) return c->fail(MOE_SPEC_EINVAL, "out is null");
+  hipError_t e = hipStreamSynchronize(c->compute);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->copy);
+  if (e != hipSuccess) return c->hip_fail(e, "synchronize");
+  int rc = c->resolve_spans();
+  if (rc) return rc;
+  unsigned long long hc[2] = {0, 0};
+  if ((e = hipMemcpy(hc, c->arena + c->lay.hit_counters, sizeof hc, hipMemcpyDeviceToHost)) != hipSuccess)
+    return c->hip_fail(e, "read hit counters");
+  c->st.hits = int64_t(hc[0]);
+  c->st.predictions = int64_t(hc[1]);
+  if (c->clock_running)
+    c->st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - c->t0).count();
+  *out = c->st;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_reset(moe_spec_ctx *c) {
+  if (!c) return MOE_SPEC_EINVAL;
+  hipError_t e = hipStreamSynchronize(c->compute);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->copy);
+  if (e != hipSuccess) return c->hip_fail(e, "synchronize");
+  int rc = c->resolve_spans();
+  if (rc) return rc;
+  for (auto &p : c->pools) {
+    std::fill(p.slot_expert.begin(), p.slot_expert.end(), -1);
+    std::fill(p.slot_stamp.begin(), p.slot_stamp.end(), -1);
+    std::fill(p.where.begin(), p.where.end(), -1);
+    p.clock = 0;
+  }
+  if ((e = hipMemsetAsync(c->arena + c->lay.hit_counters, 0, 256, c->compute)) != hipSuccess) return c->hip_fail(e, "clear counters");
+  if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
+  c->st = moe_spec_stats_t{};
+  c->clock_running = false;
+  c->token_open = false;
+  c->have_pending = false;
+  c->next_layer = 0;
+  c->pending_union.clear();
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_launch, int64_t *bytes_per_launch) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (which < 0 || which > 2 || reps < 1 || !ms_per_launch || !bytes_per_launch)
+    return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
+  const moe_spec_config &cfg = c->cfg;
+  const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter;
+  const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
+  if (which == 2) for (int l = 0; l < L; ++l) if (!c->router_w[l]) return c->fail(MOE_SPEC_ESTATE, "resident tables not set");
+  hipError_t e;
+  int32_t ids[kMaxTopK];
+  ActiveList act{};
+  act.n = k;
+  for (int j = 0; j < k; ++j) { ids[j] = j; act.expert[j] = int16_t(j); act.slot[j] = int16_t(j); }
+  if ((e = hipMemcpyAsync(c->arena + c->lay.bench_ids, ids, size_t(k) * 4, hipMemcpyHostToDevice, c->compute)) != hipSuccess)
+    return c->hip_fail(e, "upload ids");
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  if ((e = hipEventCreate(&t0)) != hipSuccess) return c->hip_fail(e, "event");
+  if ((e = hipEventCreate(&t1)) != hipSuccess) { (void)hipEventDestroy(t0); return c->hip_fail(e, "event"); }
+  ExpertArgs xa{};
+  xa.slot_bytes = c->slot_stride;
+  xa.s = c->at<float>(c->lay.s_buf);
+  xa.exec_ids = c->at<int32_t>(c->lay.bench_ids);
+  xa.exec_gates = c->at<float>(c->lay.true_gates);
+  xa.h = c->at<float>(c->lay.h);
+  xa.y = c->at<float>(c->lay.y);
+  xa.B = 1; xa.k = k; xa.H = H; xa.I = I;
+  xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
+  RouteArgs ra{};
+  ra.r = c->at<float>(c->lay.s_buf);
+  ra.z = c->at<double>(c->lay.z);
+  ra.counter = c->at<unsigned int>(c->lay.counter);
+  ra.ids_out = c->at<int32_t>(c->lay.true_ids);
+  ra.gates_out = c->at<float>(c->lay.true_gates);
+  ra.hit_counters = c->at<unsigned long long>(c->lay.hit_counters);
+  ra.B = 1; ra.H = H; ra.E = E; ra.k = k; ra.eps = cfg.rms_eps; ra.bf16 = xa.bf16;
+  hipError_t le = hipSuccess;
+  for (int pass = 0; pass < 2 && le == hipSuccess; ++pass) {      // pass 0 warms up
+    const int n = pass == 0 ? std::min(reps, 4) : reps;
+    if (pass == 1) le = hipEventRecord(t0, c->compute);
+    for (int i = 0; i < n && le == hipSuccess; ++i) {
+      const int l = i % L;
+      xa.pool = c->pool_base(l);
+      if (which == 0) le = launch_gateup(xa, act, cfg.dtype, c->compute);
+      else if (which == 1) le = launch_down(xa, act, cfg.dtype, c->compute);
+      else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
+    }
+    if (pass == 1 && le == hipSuccess) le = hipEventRecord(t1, c->compute);
+  }
+  e = hipStreamSynchronize(c->compute);
+  float ms = 0.f;
+  if (le == hipSuccess && e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  if (le != hipSuccess) return c->hip_fail(le, "kernel launch");
+  if (e != hipSuccess) return c->hip_fail(e, "timing");
+  *ms_per_launch = double(ms) / reps;
+  *bytes_per_launch = which == 0 ? int64_t(k) * 2 * I * H * wbytes
+                    : which == 1 ? int64_t(k) * I * H * wbytes
+                                 : int64_t(E) * H * wbytes;
+  return MOE_SPEC_OK;
+}
+
+}  // extern "C"

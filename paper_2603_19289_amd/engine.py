@@ -1,0 +1,126 @@
+"""Plumbing around the C ABI for tests, the smoke check and the benchmark: device memory and
+streams come from PyTorch, everything else is a call into libmoe_spec.so."""
+from __future__ import annotations
+
+import ctypes as C
+from typing import Dict, Optional
+
+import numpy as np
+import torch
+
+from . import moe_spec as M
+
+
+def _np_to_torch_storage(a: np.ndarray) -> torch.Tensor:
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16)
+    return torch.from_numpy(a)
+
+
+class Engine:
+    """Owns a context plus the torch tensors it borrows (arena, resident tables, host pool)."""
+
+    def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
+                 resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
+                 predict_in_on_demand=1, profile=0, device="cuda:0"):
+        self.dev = torch.device(device)
+        self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
+        self.max_batch = max_batch
+        self.compute = torch.cuda.Stream(device=self.dev)
+        self.copy = torch.cuda.Stream(device=self.dev)
+        cfg = M.Config(n_layers=n_layers, hidden=hidden, n_experts=n_experts, top_k=top_k, inter=inter,
+                       max_batch=max_batch, slots_per_layer=slots,
+                       dtype=M.BF16 if dtype == "bf16" else M.F32, mode=mode, rms_eps=rms_eps,
+                       q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
+                       profile=profile)
+        need = M.moe_spec_arena_bytes(cfg)
+        if need == 0:
+            raise ValueError("invalid configuration")
+        self.arena = torch.empty(need, dtype=torch.uint8, device=self.dev)
+        cfg.device_arena = self.arena.data_ptr()
+        cfg.device_arena_bytes = need
+        cfg.compute_stream = self.compute.cuda_stream
+        cfg.copy_stream = self.copy.cuda_stream
+        self.cfg = cfg
+        self.expert_bytes = M.moe_spec_expert_bytes(cfg)
+        self.ctx = M.moe_spec_create(cfg)
+
+        # resident tables
+        self.router_w = _np_to_torch_storage(resident["router_w"]).to(self.dev)
+        self.rms_gain = torch.from_numpy(np.ascontiguousarray(resident["rms_gain"], dtype=np.float32)).to(self.dev)
+        self.dvecs = _np_to_torch_storage(resident["dvecs"]).to(self.dev)
+        for l in range(n_layers):
+            M.moe_spec_set_layer_resident(self.ctx, l, self.router_w[l].data_ptr(), self.rms_gain[l].data_ptr(),
+                                          self.dvecs[l].data_ptr())
+        # host pool: [L, E, 3*H*I] in storage dtype, pinned
+        if isinstance(experts, np.ndarray):
+            t = _np_to_torch_storage(experts)
+            pool = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+            pool.copy_(t)
+        else:
+            pool = experts
+            assert pool.is_pinned()
+        self.pool = pool
+        for l in range(n_layers):
+            M.moe_spec_load_host_experts(self.ctx, l, 0, n_experts, pool[l].data_ptr(),
+                                         n_experts * self.expert_bytes)
+        torch.cuda.synchronize(self.dev)
+
+    # ------------------------------------------------------------------ calls
+    def begin_token(self):
+        M.moe_spec_begin_token(self.ctx)
+
+    def layer_step(self, layer: int, r: torch.Tensor, out: Optional[torch.Tensor] = None, want_ids=False,
+                   sync_input=True):
+        """r: [B,H] float32 on the device.  With sync_input the compute stream first waits for the
+        caller's current torch stream (where r was produced); callers that already work on
+        `self.compute` pass False."""
+        B = r.shape[0]
+        assert r.dtype == torch.float32 and r.is_contiguous() and r.shape[1] == self.H
+        if out is None:
+            out = torch.empty_like(r)
+        outs = None
+        bufs = None
+        if want_ids:
+            mk_i = lambda: torch.full((B, self.k), -1, dtype=torch.int32, device=self.dev)
+            mk_f = lambda: torch.full((B, self.k), float("nan"), dtype=torch.float32, device=self.dev)
+            bufs = {"true_ids": mk_i(), "true_gates": mk_f(), "exec_ids": mk_i(), "exec_gates": mk_f(),
+                    "next_ids": mk_i(), "next_gates": mk_f()}
+            outs = M.StepOutputs(**{k: v.data_ptr() for k, v in bufs.items()})
+        if sync_input:
+            self.compute.wait_stream(torch.cuda.current_stream(self.dev))
+        M.moe_spec_layer_step(self.ctx, layer, r.data_ptr(), B, out.data_ptr(), outs)
+        return out, bufs
+
+    def advance(self, r, out, eps, a, b, r_next=None):
+        if r_next is None:
+            r_next = torch.empty_like(r)
+        M.moe_spec_synth_advance(self.compute.cuda_stream, r.data_ptr(), out.data_ptr(), eps.data_ptr(),
+                                 a, b, r.shape[0], r.shape[1], r_next.data_ptr())
+        return r_next
+
+    def stats(self) -> dict:
+        return M.moe_spec_stats(self.ctx)
+
+    def reset(self):
+        M.moe_spec_reset(self.ctx)
+
+    def time_kernel(self, which: int, reps: int):
+        return M.moe_spec_time_kernel(self.ctx, which, reps)
+
+    def close(self):
+        if self.ctx:
+            M.moe_spec_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def engine_for(wl, mode, resident, experts, **kw) -> Engine:
+    return Engine(n_layers=wl.n_layers, hidden=wl.hidden, n_experts=wl.n_experts, top_k=wl.top_k,
+                  inter=wl.inter, dtype=wl.dtype, max_batch=kw.pop("max_batch", wl.batch), slots=wl.slots,
+                  mode=mode, resident=resident, experts=experts, **kw)

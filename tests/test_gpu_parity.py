@@ -1,0 +1,129 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU checker on the same
+seeded inputs.  Expert ids, hit counts and cache traffic must be equal; layer outputs within
+1e-5 (float32 weights) or 2e-2 (bf16 weights) relative L2 error per token row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2603_19289_amd import workload as W
+from tests.helpers import build, make_advance, small_workload
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+MODES = {"on_demand": O.MODE_ON_DEMAND, "speculative": O.MODE_SPECULATIVE}
+
+
+def rel_err(got, want):
+    return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
+
+
+def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label=""):
+    """The checker runs free; the GPU step is fed the checker's r_l at every layer."""
+    from paper_2603_19289_amd.engine import engine_for
+    print(f"[case] {label or wl.name} mode={mode} L={wl.n_layers} H={wl.hidden} E={wl.n_experts} k={wl.top_k} "
+          f"I={wl.inter} B={wl.batch} S={wl.slots} {wl.dtype}", flush=True)
+    res, ex, model = build(wl, gains)
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, mode, wl.slots, q_from_normalized=bool(q_from_normalized))
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = engine_for(wl, mode, res, ex, q_from_normalized=q_from_normalized)
+    worst = 0.0
+    try:
+        for t in range(wl.tokens):
+            eng.begin_token()
+            for l in range(wl.n_layers):
+                r_np, want = trace[t][l]
+                r = torch.from_numpy(r_np.astype(np.float32)).to("cuda")
+                out, ids = eng.layer_step(l, r, want_ids=True)
+                torch.cuda.synchronize()
+                where = f"token {t} layer {l}"
+                np.testing.assert_array_equal(ids["true_ids"].cpu().numpy(), want.true_ids, err_msg=where)
+                np.testing.assert_allclose(ids["true_gates"].cpu().numpy(), want.true_gates, atol=2e-7, rtol=1e-6, err_msg=where)
+                np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), want.exec_ids, err_msg=where)
+                np.testing.assert_allclose(ids["exec_gates"].cpu().numpy(), want.exec_gates, atol=2e-7, rtol=1e-6, err_msg=where)
+                if want.next_ids is not None:
+                    np.testing.assert_array_equal(ids["next_ids"].cpu().numpy(), want.next_ids, err_msg=where)
+                    np.testing.assert_allclose(ids["next_gates"].cpu().numpy(), want.next_gates, atol=2e-7, rtol=1e-6, err_msg=where)
+                else:
+                    assert (ids["next_ids"].cpu().numpy() == -1).all(), where
+                err = rel_err(out.cpu().numpy().astype(np.float64), want.out).max()
+                worst = max(worst, err)
+                assert err <= TOL[wl.dtype], f"{where}: relative error {err:.3e}"
+        st = eng.stats()
+        for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes"):
+            assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
+    finally:
+        eng.close()
+    print(f"[ok] worst relative error {worst:.3e}; hits {orc.stats.hits}/{orc.stats.predictions}; "
+          f"cache {orc.stats.cache_hits} hits {orc.stats.cache_misses} misses", flush=True)
+    return worst
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+def test_c1_tiny_fp32(mode):
+    wl = W.CONFIGS["c1_tiny"]
+    run_teacher_forced(wl, MODES[mode], gains="ones")
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+def test_c1_tiny_fp32_per_layer_default_vector(mode):
+    # the literal reading of the workload text: one default vector per layer, shared by all experts
+    run_teacher_forced(W.CONFIGS["c1_tiny"].with_(per_layer_dvec=True, tokens=8), MODES[mode], gains="ones")
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_shapes_single_token(mode, dtype):
+    # H, I not multiples of the 512/256-element wave strides, E not a multiple of rows per block
+    wl = small_workload(name="ragged", n_layers=4, hidden=328, n_experts=21, top_k=3, inter=136,
+                        dtype=dtype, batch=1, tokens=6, slots=5, seed=11)
+    run_teacher_forced(wl, MODES[mode])
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("B,S", [(3, 6), (5, 4), (8, 3)])
+def test_batches_and_cache_waves(mode, B, S):
+    # S smaller than the union of routed experts forces several cache waves per layer
+    wl = small_workload(name="waves", n_layers=3, hidden=264, n_experts=12, top_k=3, inter=200,
+                        dtype="bf16", batch=B, tokens=4, slots=S, seed=5)
+    run_teacher_forced(wl, MODES[mode])
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+def test_edge_shapes(mode):
+    # every expert selected; pool exactly k; one expert; one layer (no prediction at all)
+    run_teacher_forced(small_workload(name="all_experts", n_experts=4, top_k=4, slots=4, tokens=3, dtype="f32"), MODES[mode])
+    run_teacher_forced(small_workload(name="one_expert", n_experts=1, top_k=1, slots=1, tokens=3), MODES[mode])
+    run_teacher_forced(small_workload(name="one_layer", n_layers=1, tokens=3), MODES[mode])
+    run_teacher_forced(small_workload(name="wide_router", n_experts=200, top_k=16, slots=16, tokens=2, hidden=128), MODES[mode])
+    run_teacher_forced(small_workload(name="max_batch", batch=64, n_experts=16, top_k=2, slots=8, tokens=2, dtype="f32"), MODES[mode])
+
+
+@pytest.mark.parametrize("mode", list(MODES))
+def test_caption_reading_of_the_quasi_hidden_state(mode):
+    run_teacher_forced(small_workload(name="caption", n_layers=4, tokens=4), MODES[mode], q_from_normalized=1)
+
+
+def test_crafted_ties_pick_the_lower_index():
+    # identical router rows give exactly equal logits: the lower expert index must win on the GPU too
+    from paper_2603_19289_amd.engine import engine_for
+    wl = small_workload(name="ties", n_layers=2, n_experts=8, top_k=3, tokens=2, dtype="f32")
+    res, ex, model = build(wl)
+    res["router_w"][:, 5] = res["router_w"][:, 2]
+    res["router_w"][:, 7] = res["router_w"][:, 2]
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots)
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = engine_for(wl, O.MODE_ON_DEMAND, res, ex)
+    try:
+        for t in range(wl.tokens):
+            eng.begin_token()
+            for l in range(wl.n_layers):
+                r = torch.from_numpy(trace[t][l][0].astype(np.float32)).cuda()
+                _, ids = eng.layer_step(l, r, want_ids=True)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(ids["true_ids"].cpu().numpy(), trace[t][l][1].true_ids)
+    finally:
+        eng.close()
