@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-time MoE layer step with speculative expert prefetch on one MI355X.
+
+A "step" is one decode token: all L layer steps of the hot path (route, predict, prefetch,
+expert GEMVs, combine) for one batch of synthetic input, with expert weights already resident
+in the pinned host pool and everything else in HBM.  The headline value is tokens/s in
+speculative mode; on-demand loading is measured beside it on the same tokens, interleaved.
+
+Prints one JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=48, help="timed decode tokens per mode per repetition")
+    p.add_argument("--warmup", type=int, default=4, help="untimed decode tokens before each timed run")
+    p.add_argument("--reps", type=int, default=3, help="interleaved A/B repetitions")
+    p.add_argument("--workload", default="c2_qwen3_30b_a3b")
+    p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
+    p.add_argument("--cpu-tokens", type=int, default=2, help="tokens the CPU checker is timed on (0 = skip)")
+    p.add_argument("--kernel-reps", type=int, default=480)
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1.  How the path would shard is described in DESIGN.md.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2603_19289_amd import moe_spec as M
+    from paper_2603_19289_amd import workload as W
+    from paper_2603_19289_amd.engine import engine_for
+
+    M.lib()          # fail loudly if the HIP library is missing
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+
+    wl = W.CONFIGS[args.workload]
+    reduced = bool(args.layers) and args.layers != wl.n_layers
+    if args.layers:
+        wl = wl.with_(n_layers=args.layers)
+    K, Wm, B, L, H = args.steps, args.warmup, wl.batch, wl.n_layers, wl.hidden
+    T = K + Wm
+
+    t_setup = time.time()
+    res = W.make_resident(wl)
+    tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    pool = torch.empty((L, wl.n_experts, wl.expert_elems), dtype=tdtype, pin_memory=True)
+    W.fill_experts_gpu(wl, pool)
+    x0_np, eps_np = W.make_inputs(wl, tokens=T)
+    x0 = torch.from_numpy(x0_np).to(dev)
+    eps = torch.from_numpy(eps_np).to(dev)
+    log(f"[bench] {wl.name}: pool {pool.numel() * pool.element_size() / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
+
+    def make(mode, profile):
+        return engine_for(wl, mode, res, pool, predict_in_on_demand=0, profile=profile)
+
+    engines = {"speculative": make(M.MODE_SPECULATIVE, 0), "on_demand": make(M.MODE_ON_DEMAND, 0)}
+
+    def run_tokens(eng, t_first, n):
+        out = torch.empty((B, H), dtype=torch.float32, device=dev)
+        rbuf = [torch.empty((B, H), dtype=torch.float32, device=dev) for _ in range(2)]
+        with torch.cuda.stream(eng.compute):
+            for t in range(t_first, t_first + n):
+                eng.begin_token()
+                r = x0[t]
+                for l in range(L):
+                    eng.layer_step(l, r, out, sync_input=False)
+                    if l + 1 < L:
+                        r = eng.advance(r, out, eps[t, l], wl.res_a, wl.res_b, rbuf[l & 1])
+
+    def timed(eng):
+        eng.reset()
+        run_tokens(eng, 0, Wm)
+        torch.cuda.synchronize()
+        before = eng.stats()
+        t0 = time.perf_counter()
+        run_tokens(eng, Wm, K)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        after = eng.stats()
+        d = {k: after[k] - before[k] for k in after}
+        return dt, d
+
+    results = {m: [] for m in engines}
+    for rep in range(args.reps):
+        for mode, eng in engines.items():
+            dt, d = timed(eng)
+            results[mode].append((dt, d))
+            log(f"[bench] rep {rep} {mode}: TPOT {dt / K * 1e3:.3f} ms, H2D {d['h2d_bytes'] / dt / 1e9:.2f} GB/s "
+                f"({d['cache_misses']} misses, {d['cache_hits']} hits)")
+
+    def summary(mode):
+        tp = np.array([dt / K * 1e3 for dt, _ in results[mode]])
+        d = results[mode][-1][1]
+        dt = results[mode][-1][0]
+        return {"tpot_ms": float(tp.mean()), "tpot_ms_std": float(tp.std()), "tokens_per_s": float(B / (tp.mean() / 1e3)),
+                "h2d_gb_per_token": d["h2d_bytes"] / K / 1e9, "h2d_gbs_wall": d["h2d_bytes"] / dt / 1e9,
+                "link_frac_wall_nominal": d["h2d_bytes"] / dt / 1e9 / LINK_PEAK_GBS,
+                "cache_hit_rate": d["cache_hits"] / max(1, d["cache_hits"] + d["cache_misses"]),
+                "hbm_gb_algorithmic_per_token": d["hbm_bytes_algorithmic"] / K / 1e9}
+
+    spec, ond = summary("speculative"), summary("on_demand")
+
+    # ---- breakdown with timing events (separate, instrumented contexts) and hit statistics
+    breakdown = {}
+    for mode, code in (("speculative", M.MODE_SPECULATIVE), ("on_demand", M.MODE_ON_DEMAND)):
+        engines[mode].close()
+        eng = engine_for(wl, code, res, pool, predict_in_on_demand=1, profile=1)
+        dt, d = timed(eng)
+        busy = d["copy_ms"]
+        breakdown[mode] = {
+            "wall_ms_per_token": dt / K * 1e3, "copy_ms_per_token": d["copy_ms"] / K,
+            "compute_ms_per_token": d["compute_ms"] / K, "stall_ms_per_token": d["stall_ms"] / K,
+            "idle_ms_per_token": max(0.0, (dt * 1e3 - d["copy_ms"] - d["compute_ms"]) / K) if mode == "on_demand" else None,
+            "h2d_gbs_while_copying": d["h2d_bytes"] / (busy / 1e3) / 1e9 if busy > 0 else None,
+            "link_frac_while_copying_nominal": d["h2d_bytes"] / (busy / 1e3) / 1e9 / LINK_PEAK_GBS if busy > 0 else None,
+            "overlap_fraction": ((d["copy_ms"] + d["compute_ms"] - dt * 1e3) / min(d["copy_ms"], d["compute_ms"]))
+            if min(d["copy_ms"], d["compute_ms"]) > 0 else None,
+            "hit_rate_recall_at_k": d["hits"] / max(1, d["predictions"])}
+        if mode == "on_demand":
+            eng.close()
+        else:
+            prof_eng = eng
+
+    # ---- roofline of the dominant kernel (gate/up GEMV) and of the other two, on cold slots
+    kern = {}
+    for which, name in ((0, "expert_gateup_gemv"), (1, "expert_down_gemv"), (2, "router")):
+        ms, nbytes = prof_eng.time_kernel(which, args.kernel_reps)
+        kern[name] = {"ms_per_launch": ms, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
+    prof_eng.close()
+    dom = kern["expert_gateup_gemv"]
+    roofline = {"bound": "hbm", "kernel": "gateup_kernel (expert W_gate/W_up GEMV + SwiGLU)", "achieved": dom["gbs"],
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None,
+                "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"}}
+
+    # ---- the CPU checker timed on this host, on a bounded prefix of the same workload
+    cpu = None
+    if args.cpu_tokens > 0:
+        from oracle import moe_oracle as O
+        n_tok = min(args.cpu_tokens, T)
+        pool_np = pool.view(torch.int16).numpy().view(np.uint16) if wl.dtype == "bf16" else pool.numpy()
+        model = O.OracleModel(n_layers=L, hidden=H, n_experts=wl.n_experts, top_k=wl.top_k, inter=wl.inter,
+                              dtype=O.DTYPE_BF16 if wl.dtype == "bf16" else O.DTYPE_F32, router_w=res["router_w"],
+                              rms_gain=res["rms_gain"], dvecs=res["dvecs"], experts=pool_np)
+        orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
+        t0 = time.perf_counter()
+        O.run_tokens(orc, x0_np[:n_tok], lambda t, l, r, o: W.advance_residual(wl, r, o, eps_np[t, l]))
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        except Exception:
+            threads = os.cpu_count()
+        cpu = {"value": B * n_tok / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"first {n_tok} decode tokens of the same workload (all {L} layers, speculative mode), "
+                         f"{dt:.1f} s of numpy float64 on the host"}
+
+    line = {
+        "metric": "decode tokens/s with speculative expert prefetch (TPOT in ms_per_step); on-demand loading beside it",
+        "value": spec["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": spec["tpot_ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name + (" (REDUCED LAYERS, development run)" if reduced else ""),
+                   "layers": L, "hidden": H, "experts": wl.n_experts, "top_k": wl.top_k, "inter": wl.inter,
+                   "batch": B, "slots_per_layer": wl.slots, "reps": args.reps,
+                   "expert_bytes": wl.expert_bytes, "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9},
+        "speculative": spec, "on_demand": ond,
+        "tpot_reduction_vs_on_demand": 1.0 - spec["tpot_ms"] / ond["tpot_ms"],
+        "breakdown_instrumented": breakdown,
+        "link": {"peak_nominal_gbs": LINK_PEAK_GBS, "achieved_gbs_speculative_wall": spec["h2d_gbs_wall"],
+                 "achieved_gbs_on_demand_wall": ond["h2d_gbs_wall"]},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
