@@ -36,6 +36,7 @@ def parse():
     p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
     p.add_argument("--cpu-tokens", type=int, default=2, help="tokens the CPU checker is timed on (0 = skip)")
     p.add_argument("--kernel-reps", type=int, default=480)
+    p.add_argument("--copy-engine", choices=["kernel", "dma"], default="kernel")
     return p.parse_args()
 
 
@@ -74,8 +75,10 @@ def main():
     eps = torch.from_numpy(eps_np).to(dev)
     log(f"[bench] {wl.name}: pool {pool.numel() * pool.element_size() / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
 
+    copy_engine = M.COPY_KERNEL if args.copy_engine == "kernel" else M.COPY_DMA
+
     def make(mode, profile):
-        return engine_for(wl, mode, res, pool, predict_in_on_demand=0, profile=profile)
+        return engine_for(wl, mode, res, pool, predict_in_on_demand=0, profile=profile, copy_engine=copy_engine)
 
     engines = {"speculative": make(M.MODE_SPECULATIVE, 0), "on_demand": make(M.MODE_ON_DEMAND, 0)}
 
@@ -128,7 +131,7 @@ def main():
     breakdown = {}
     for mode, code in (("speculative", M.MODE_SPECULATIVE), ("on_demand", M.MODE_ON_DEMAND)):
         engines[mode].close()
-        eng = engine_for(wl, code, res, pool, predict_in_on_demand=1, profile=1)
+        eng = engine_for(wl, code, res, pool, predict_in_on_demand=1, profile=1, copy_engine=copy_engine)
         dt, d = timed(eng)
         busy = d["copy_ms"]
         breakdown[mode] = {
@@ -185,7 +188,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + (" (REDUCED LAYERS, development run)" if reduced else ""),
                    "layers": L, "hidden": H, "experts": wl.n_experts, "top_k": wl.top_k, "inter": wl.inter,
-                   "batch": B, "slots_per_layer": wl.slots, "reps": args.reps,
+                   "batch": B, "slots_per_layer": wl.slots, "reps": args.reps, "copy_engine": args.copy_engine,
                    "expert_bytes": wl.expert_bytes, "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9},
         "speculative": spec, "on_demand": ond,
         "tpot_reduction_vs_on_demand": 1.0 - spec["tpot_ms"] / ond["tpot_ms"],

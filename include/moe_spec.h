@@ -43,6 +43,7 @@ enum { MOE_SPEC_OK = 0, MOE_SPEC_EINVAL = -1, MOE_SPEC_ENOMEM = -2, MOE_SPEC_EST
        MOE_SPEC_EHIP = -4 };
 enum { MOE_SPEC_MODE_ON_DEMAND = 0, MOE_SPEC_MODE_SPECULATIVE = 1 };
 enum { MOE_SPEC_F32 = 0, MOE_SPEC_BF16 = 1 };   /* storage type of every weight table */
+enum { MOE_SPEC_COPY_DMA = 0, MOE_SPEC_COPY_KERNEL = 1 };
 
 /* limits checked by moe_spec_create */
 #define MOE_SPEC_MAX_EXPERTS 256
@@ -63,7 +64,10 @@ typedef struct {
                                        hit statistics exist; 0 skips it (timing runs) */
   int32_t profile;                  /* 1: bracket copies and kernels with timing events and fill
                                        copy_ms / compute_ms / stall_ms (adds a sync per token) */
-  int32_t reserved0;
+  int32_t copy_engine;              /* how experts travel host -> device on the copy stream:
+                                       0: one hipMemcpyAsync per expert (DMA engine);
+                                       1: one gather-copy kernel per request that reads the pinned
+                                          pool directly (a few workgroups; keeps the link busier) */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
   size_t  device_arena_bytes;
   void   *compute_stream;           /* hipStream_t, borrowed; kernels run here */

@@ -199,6 +199,30 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
   a.out[size_t(b) * a.H + i] = acc;
 }
 
+// Host-to-device copy of whole expert blocks by a few workgroups that read the pinned pool
+// directly.  blockIdx.y picks the block, the workgroups of a row share it in 16-byte units.
+// UNROLL loads are in flight per lane; the launch keeps the bytes in flight near the link's
+// bandwidth-delay product, because host reads that queue up in the memory system delay the
+// HBM requests of kernels running beside the copy.
+template <int UNROLL>
+__global__ __launch_bounds__(kBlock) void gather_copy_kernel(const CopyList cl) {
+  const uint4 *src = static_cast<const uint4 *>(cl.src[blockIdx.y]);
+  uint4 *dst = static_cast<uint4 *>(cl.dst[blockIdx.y]);
+  const uint32_t n = cl.n16;
+  const uint32_t stride = gridDim.x * kBlock;
+  uint32_t i = blockIdx.x * kBlock + threadIdx.x;
+  if (UNROLL > 1) {
+    for (; i + (UNROLL - 1) * stride < n; i += UNROLL * stride) {
+      uint4 v[UNROLL];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) v[u] = src[i + u * stride];
+#pragma unroll
+      for (int u = 0; u < UNROLL; ++u) dst[i + u * stride] = v[u];
+    }
+  }
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
 int pick_tok_tile(int B, int row_len) {
   int tt = 1;
   while (tt < B && tt < 8) tt <<= 1;
@@ -261,6 +285,20 @@ hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, 
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
   if (act.n <= 0) return hipSuccess;
   return dtype == 1 ? launch_down_t<uint16_t>(a, act, st) : launch_down_t<float>(a, act, st);
+}
+
+hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st) {
+  if (cl.n <= 0) return hipSuccess;
+  int total = cl.total_wgs > 0 ? cl.total_wgs : 32;
+  int wg_per_block = (total + cl.n - 1) / cl.n;
+  if (wg_per_block < 1) wg_per_block = 1;
+  const dim3 grid(wg_per_block, cl.n), block(kBlock);
+  switch (cl.unroll) {
+    case 4: hipLaunchKernelGGL(gather_copy_kernel<4>, grid, block, 0, st, cl); break;
+    case 2: hipLaunchKernelGGL(gather_copy_kernel<2>, grid, block, 0, st, cl); break;
+    default: hipLaunchKernelGGL(gather_copy_kernel<1>, grid, block, 0, st, cl); break;
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_combine(const ExpertArgs &a, hipStream_t st) {

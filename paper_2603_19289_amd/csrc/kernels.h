@@ -67,6 +67,17 @@ struct ExpertArgs {
   int B, k, H, I, bf16, tok_tile;
 };
 
+// Host-to-device gather copy: each entry moves one expert block from the pinned pool to a slot.
+constexpr int kCopyListMax = 32;
+struct CopyList {
+  const void *src[kCopyListMax];   // host (pinned, device-visible)
+  void *dst[kCopyListMax];         // device slot
+  int32_t n;
+  uint32_t n16;                    // 16-byte units per block
+  int32_t total_wgs, unroll;       // launch shape: workgroups over all blocks, loads in flight per lane
+};
+hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st);
+
 hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);

@@ -16,6 +16,7 @@
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <deque>
 #include <new>
@@ -59,6 +60,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->dtype != MOE_SPEC_F32 && c->dtype != MOE_SPEC_BF16) return "unknown dtype";
   if (c->mode != MOE_SPEC_MODE_ON_DEMAND && c->mode != MOE_SPEC_MODE_SPECULATIVE) return "unknown mode";
   if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
+  if (c->copy_engine != MOE_SPEC_COPY_DMA && c->copy_engine != MOE_SPEC_COPY_KERNEL) return "unknown copy_engine";
   return nullptr;
 }
 
@@ -104,6 +106,7 @@ struct moe_spec_ctx {
   Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
   Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
   uint32_t seq = 0;
+  int copy_wgs = 16, copy_unroll = 2;   // gather-copy launch shape (see launch_gather_copy)
 
   // token state
   bool token_open = false;
@@ -204,6 +207,10 @@ struct moe_spec_ctx {
     act->n = 0;
     int copies = 0;
     TimedSpan *span = nullptr;
+    CopyList cl{};
+    cl.n16 = uint32_t(expert_bytes / 16);
+    cl.total_wgs = copy_wgs;
+    cl.unroll = copy_unroll;
     for (int e : experts) {
       if (p.where[e] >= 0) { p.slot_stamp[p.where[e]] = int(p.clock); st.cache_hits += 1; }
     }
@@ -229,12 +236,26 @@ struct moe_spec_ctx {
       p.slot_expert[victim] = e;
       p.slot_stamp[victim] = int(p.clock);
       p.where[e] = victim;
-      hipError_t c = hipMemcpyAsync(pool_base(layer) + size_t(victim) * slot_stride, src, expert_bytes,
-                                    hipMemcpyHostToDevice, copy);
-      if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
+      char *dst = pool_base(layer) + size_t(victim) * slot_stride;
+      if (cfg.copy_engine == MOE_SPEC_COPY_KERNEL) {
+        cl.src[cl.n] = src;
+        cl.dst[cl.n] = dst;
+        if (++cl.n == kCopyListMax) {
+          hipError_t c = launch_gather_copy(cl, copy);
+          if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
+          cl.n = 0;
+        }
+      } else {
+        hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, copy);
+        if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
+      }
       copies += 1;
       st.cache_misses += 1;
       st.h2d_bytes += int64_t(expert_bytes);
+    }
+    if (cl.n > 0) {
+      hipError_t c = launch_gather_copy(cl, copy);
+      if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
     }
     if (copies > 0) {
       close_span(span, copy);
@@ -299,6 +320,8 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   c->expert_bytes = expert_bytes_of(cfg);
   c->slot_stride = align_up(c->expert_bytes, 256);
   c->arena = static_cast<char *>(cfg->device_arena);
+  if (const char *v = getenv("MOE_SPEC_COPY_WGS")) c->copy_wgs = std::max(1, atoi(v));        // tuning knobs
+  if (const char *v = getenv("MOE_SPEC_COPY_UNROLL")) c->copy_unroll = std::max(1, atoi(v));
   c->compute = static_cast<hipStream_t>(cfg->compute_stream);
   c->copy = static_cast<hipStream_t>(cfg->copy_stream);
   const int L = cfg->n_layers, E = cfg->n_experts, S = cfg->slots_per_layer;
@@ -383,9 +406,18 @@ int moe_spec_load_host_experts(moe_spec_ctx *c, int layer, int first_expert, int
     (void)hipGetLastError();
     return c->fail(MOE_SPEC_EINVAL, "host pool must be page-locked (pinned) host memory");
   }
+  const char *base = static_cast<const char *>(pinned_host);
+  if (c->cfg.copy_engine == MOE_SPEC_COPY_KERNEL) {     // the address the copy kernel reads the pool at
+    void *dev_view = nullptr;
+    e = hipHostGetDevicePointer(&dev_view, const_cast<void *>(pinned_host), 0);
+    if (e != hipSuccess || !dev_view) {
+      (void)hipGetLastError();
+      return c->fail(MOE_SPEC_EINVAL, "host pool is not mapped into the device address space");
+    }
+    base = static_cast<const char *>(dev_view);
+  }
   for (int i = 0; i < n_experts; ++i)
-    c->host_expert[size_t(layer) * c->cfg.n_experts + first_expert + i] =
-        static_cast<const char *>(pinned_host) + size_t(i) * c->expert_bytes;
+    c->host_expert[size_t(layer) * c->cfg.n_experts + first_expert + i] = base + size_t(i) * c->expert_bytes;
   return MOE_SPEC_OK;
 }
 

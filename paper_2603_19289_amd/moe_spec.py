@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_spec.so")
 OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 MODE_ON_DEMAND, MODE_SPECULATIVE = 0, 1
 F32, BF16 = 0, 1
+COPY_DMA, COPY_KERNEL = 0, 1
 
 
 class Config(C.Structure):
@@ -20,7 +21,7 @@ class Config(C.Structure):
                 ("top_k", C.c_int32), ("inter", C.c_int32), ("max_batch", C.c_int32),
                 ("slots_per_layer", C.c_int32), ("dtype", C.c_int32), ("mode", C.c_int32),
                 ("rms_eps", C.c_float), ("q_from_normalized", C.c_int32),
-                ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("reserved0", C.c_int32),
+                ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
 
