@@ -188,6 +188,158 @@ __global__ __launch_bounds__(kBlock) void down_kernel(const ExpertArgs a, const 
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Batch-1 kernels: no token lists, no staging barrier in the gate/up kernel, combine fused into
+// the down kernel.  These are the kernels of the headline workload.
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 64 lanes, result in every lane: two quad permutes and two mirrors inside each row of
+// 16 lanes (data-parallel primitives, no LDS traffic), then one lane of each row through scalars.
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v += dpp_move<0xB1>(v);     // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);     // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);    // row_half_mirror
+  v += dpp_move<0x140>(v);    // row_mirror
+  const int i = __float_as_int(v);
+  return __int_as_float(__builtin_amdgcn_readlane(i, 0)) + __int_as_float(__builtin_amdgcn_readlane(i, 16)) +
+         __int_as_float(__builtin_amdgcn_readlane(i, 32)) + __int_as_float(__builtin_amdgcn_readlane(i, 48));
+}
+
+// Raw 16-byte weight chunks: kept packed in registers while in flight, unpacked at use.
+template <typename WT> struct Raw;
+template <> struct Raw<uint16_t> {
+  using T = uint4;
+  static constexpr int N = 8;
+  __device__ static void unpack(const uint4 &v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+  __device__ static uint16_t pack_one(float x) { return uint16_t(__float_as_uint(x) >> 16); }   // x is bf16-exact
+};
+template <> struct Raw<float> {
+  using T = float4;
+  static constexpr int N = 4;
+  __device__ static void unpack(const float4 &v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+  __device__ static float pack_one(float x) { return x; }
+};
+
+// hq[pos, row] for the one token of the batch, stored in the weight dtype for the down kernel.
+// `act` is in execution-position order, so blockIdx.y is the position.  Each lane keeps its NCH
+// chunks of s_l in registers; a wavefront owns `rpw` consecutive rows and keeps the 2*NCH
+// 16-byte loads of the next row in flight while it reduces the current one.
+template <typename WT, int NCH>
+__global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, const ActiveList act,
+                                                           const int rpw) {
+  using R = Raw<WT>;
+  constexpr int VN = R::N;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int H = a.H, I = a.I;
+  const int row0 = (blockIdx.x * kWaves + wave) * rpw;
+  if (row0 >= I) return;
+  const int row_end = min(row0 + rpw, I);
+  const int pos = blockIdx.y;
+  const WT *wg = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[pos]) * a.slot_bytes);
+  const WT *wu = wg + size_t(I) * H;
+  WT *hq = reinterpret_cast<WT *>(a.h) + size_t(pos) * I;
+
+  int col[NCH];
+  bool live[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    col[ch] = (ch * kWave + lane) * VN;
+    live[ch] = col[ch] < H;
+    if (!live[ch]) col[ch] = 0;                // dead lanes re-read column 0 and multiply by zero
+  }
+  typename R::T rg[NCH], ru[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    rg[ch] = *reinterpret_cast<const typename R::T *>(wg + size_t(row0) * H + col[ch]);
+    ru[ch] = *reinterpret_cast<const typename R::T *>(wu + size_t(row0) * H + col[ch]);
+  }
+  float sv[NCH][VN];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+#pragma unroll
+    for (int x = 0; x < VN; x += 4) {
+      const float4 f = *reinterpret_cast<const float4 *>(a.s + col[ch] + x);
+      const float m = live[ch] ? 1.f : 0.f;
+      sv[ch][x] = f.x * m; sv[ch][x + 1] = f.y * m; sv[ch][x + 2] = f.z * m; sv[ch][x + 3] = f.w * m;
+    }
+  }
+  for (int row = row0; row < row_end; ++row) {
+    float ag = 0.f, au = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      float fg[VN], fu[VN];
+      R::unpack(rg[ch], fg);
+      R::unpack(ru[ch], fu);
+#pragma unroll
+      for (int x = 0; x < VN; ++x) { ag += fg[x] * sv[ch][x]; au += fu[x] * sv[ch][x]; }
+    }
+    if (row + 1 < row_end) {
+#pragma unroll
+      for (int ch = 0; ch < NCH; ++ch) {
+        rg[ch] = *reinterpret_cast<const typename R::T *>(wg + size_t(row + 1) * H + col[ch]);
+        ru[ch] = *reinterpret_cast<const typename R::T *>(wu + size_t(row + 1) * H + col[ch]);
+      }
+    }
+    const float g = wave_sum_dpp(ag);
+    const float u = wave_sum_dpp(au);
+    if (lane == 0) {
+      float hv = g / (1.f + expf(-g)) * u;
+      if (a.bf16) hv = round_to_bf16(hv);
+      hq[row] = R::pack_one(hv);
+    }
+  }
+}
+
+// O[row] = sum_j gate_j * (W_down_{e_j}[row,:] . hq[j,:]) for the one token of the batch: the down
+// projection of all k executed experts and the gate-weighted combine in one pass, no LDS and no
+// barrier.  One wavefront owns one output row.  The k rows it needs (one per expert, I values
+// each) are walked as one flat list of 16-byte chunks so that all 64 lanes load on every
+// iteration whatever I is; each lane folds the gate of its chunk's expert into its partial
+// sum, and a single reduction per row remains.  `act` is in execution-position order.
+template <typename WT>
+__global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArgs a, const ActiveList act,
+                                                                 const float inv_chunks) {
+  using R = Raw<WT>;
+  constexpr int VN = R::N;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int H = a.H, I = a.I, k = a.k;
+  const int row = blockIdx.x * kWaves + wave;
+  if (row >= H) return;
+  const int chunks = I / VN;                   // per expert row
+  const int total = chunks * k;
+  const WT *hq = reinterpret_cast<const WT *>(a.h);
+  const size_t down_off = (size_t(2) * I * H + size_t(row) * I) * sizeof(WT);
+  float acc = 0.f;
+#pragma unroll 4
+  for (int t = lane; t < total; t += kWave) {
+    int j = int(float(t) * inv_chunks);        // t / chunks, fixed up below (t < 2^24 is exact in float)
+    j -= (j * chunks > t);
+    j += ((j + 1) * chunks <= t);
+    const int c = (t - j * chunks) * VN;
+    const char *base = a.pool + size_t(act.slot[j]) * a.slot_bytes + down_off;
+    const typename R::T w = *reinterpret_cast<const typename R::T *>(base + size_t(c) * sizeof(WT));
+    const typename R::T hh = *reinterpret_cast<const typename R::T *>(hq + size_t(j) * I + c);
+    float fw[VN], fh[VN];
+    R::unpack(w, fw);
+    R::unpack(hh, fh);
+    float part = 0.f;
+#pragma unroll
+    for (int x = 0; x < VN; ++x) part += fw[x] * fh[x];
+    acc += a.exec_gates[j] * part;
+  }
+  const float v = wave_sum_dpp(acc);
+  if (lane == 0) a.out[row] = v;
+}
+
 // O[b, i] = sum_j gates[b, j] * y[b, j, i]
 __global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
   const int i = blockIdx.x * kBlock + threadIdx.x;
@@ -269,6 +421,37 @@ hipError_t launch_down_t(const ExpertArgs &a, const ActiveList &act, hipStream_t
   return hipGetLastError();
 }
 
+template <typename WT, int NCH>
+void launch_gateup_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  // one row per wavefront until that would exceed about 6144 wavefronts (24 per compute unit)
+  long rpw = (long(a.I) * act.n + 6143) / 6144;
+  if (rpw < 1) rpw = 1;
+  const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
+  hipLaunchKernelGGL((gateup_b1_kernel<WT, NCH>), grid, block, 0, st, a, act, int(rpw));
+}
+
+// Returns false when H needs more register chunks than the batch-1 kernel is built for.
+template <typename WT>
+bool launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  constexpr int VN = Raw<WT>::N;
+  const int need = (a.H + kWave * VN - 1) / (kWave * VN);
+  if (need <= 1) launch_gateup_b1_n<WT, 1>(a, act, st);
+  else if (need <= 2) launch_gateup_b1_n<WT, 2>(a, act, st);
+  else if (need <= 4) launch_gateup_b1_n<WT, 4>(a, act, st);
+  else if (need <= 6) launch_gateup_b1_n<WT, 6>(a, act, st);
+  else if (need <= 8) launch_gateup_b1_n<WT, 8>(a, act, st);
+  else if (need <= 16) launch_gateup_b1_n<WT, 16>(a, act, st);
+  else return false;
+  return true;
+}
+
+template <typename WT>
+void launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  const dim3 grid((a.H + kWaves - 1) / kWaves), block(kBlock);
+  const float inv_chunks = 1.0f / float(a.I / Raw<WT>::N);
+  hipLaunchKernelGGL((down_combine_b1_kernel<WT>), grid, block, 0, st, a, act, inv_chunks);
+}
+
 template <typename K>
 hipError_t allow_big_lds(K kernel) {
   return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -280,6 +463,22 @@ hipError_t allow_big_lds(K kernel) {
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
   if (act.n <= 0) return hipSuccess;
   return dtype == 1 ? launch_gateup_t<uint16_t>(a, act, st) : launch_gateup_t<float>(a, act, st);
+}
+
+// Batch 1, `act` in execution-position order.  H up to 64*16 chunks (8192 bf16 / 4096 float32 columns).
+bool b1_supported(int H, int dtype) { return H <= kWave * 16 * (dtype == 1 ? 8 : 4); }
+
+hipError_t launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
+  const bool ok = dtype == 1 ? launch_gateup_b1<uint16_t>(a, act, st) : launch_gateup_b1<float>(a, act, st);
+  return ok ? hipGetLastError() : hipErrorInvalidValue;
+}
+
+// Batch 1: down projection and combine in one kernel (the k executed experts are always one cache
+// wave); reads the hq written by launch_gateup_b1.
+hipError_t launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
+  if (dtype == 1) launch_down_combine_b1<uint16_t>(a, act, st);
+  else launch_down_combine_b1<float>(a, act, st);
+  return hipGetLastError();
 }
 
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {

@@ -82,6 +82,9 @@ hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_combine(const ExpertArgs &a, hipStream_t st);
+bool b1_supported(int H, int dtype);
+hipError_t launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
+hipError_t launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t init_kernels();     // one-time function attributes (dynamic LDS limits)
 
 size_t route_lds_bytes(int H, int B, int *tok_tile);

@@ -113,6 +113,7 @@ struct moe_spec_ctx {
   int next_layer = 0, batch = 0;
   bool have_pending = false;                    // a prediction for next_layer sits on the device
   std::vector<int> pending_union;               // sorted union of predicted ids (host copy)
+  std::vector<int> pending_ids;                 // the predicted ids [B,k] in position order (host copy)
   ActiveList pending_wave0{};                   // slots of its first wave (already requested)
 
   // statistics
@@ -508,17 +509,19 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   c->close_span(sp_route, c->compute);
 
   // --- which experts run, and where their ids and gates live on the device
-  std::vector<int> exec_union;
+  std::vector<int> exec_union, exec_ids_host;
   const int32_t *exec_ids_dev;
   const float *exec_gates_dev;
   if (exec_pred) {
     exec_union = c->pending_union;
+    exec_ids_host = c->pending_ids;
     exec_ids_dev = c->at<int32_t>(c->lay.pend_ids[layer & 1]);
     exec_gates_dev = c->at<float>(c->lay.pend_gates[layer & 1]);
   } else {
     int rc = c->wait_mailbox(c->mb_true, ticket_true);
     if (rc) return rc;
     exec_union = moe_spec_ctx::sorted_union(c->mb_true->ids, batch * k);
+    exec_ids_host.assign(c->mb_true->ids, c->mb_true->ids + batch * k);
     exec_ids_dev = c->at<int32_t>(c->lay.true_ids);
     exec_gates_dev = c->at<float>(c->lay.true_gates);
   }
@@ -543,6 +546,8 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   xa.B = batch; xa.k = k; xa.H = H; xa.I = I;
   xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
 
+  const bool fast_b1 = batch == 1 && b1_supported(H, cfg.dtype);
+
   // --- cache waves: make resident (unless prefetched), wait, run
   TimedSpan *sp_stall = c->open_span(2, c->compute);
   bool stall_open = sp_stall != nullptr;
@@ -563,13 +568,25 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     if (need_wait && (e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess)
       return c->hip_fail(e, "compute stream wait");
     if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
-    if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
-    if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+    if (fast_b1) {
+      // batch 1: the k executed experts are one wave; hand the kernels the slots in position order
+      ActiveList by_pos{};
+      by_pos.n = k;
+      for (int j = 0; j < k; ++j) {
+        by_pos.expert[j] = int16_t(exec_ids_host[j]);
+        by_pos.slot[j] = int16_t(c->pools[layer].where[exec_ids_host[j]]);
+      }
+      if ((e = launch_gateup_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+      if ((e = launch_down_combine_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+    } else {
+      if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+      if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+    }
     if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
     c->done_recorded[layer] = 1;
     c->st.hbm_bytes_algorithmic += int64_t(act.n) * int64_t(c->expert_bytes);
   }
-  if ((e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
+  if (!fast_b1 && (e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
   c->close_span(sp_exec, c->compute);
 
   // --- prefetch the first wave of the predicted experts of layer l+1
@@ -578,6 +595,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     int rc = c->wait_mailbox(c->mb_next, ticket_next);
     if (rc) return rc;
     c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
+    c->pending_ids.assign(c->mb_next->ids, c->mb_next->ids + batch * k);
     std::vector<int> req(c->pending_union.begin(),
                          c->pending_union.begin() + std::min<size_t>(c->pending_union.size(), S));
     int copies = 0;
@@ -664,6 +682,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   xa.exec_gates = c->at<float>(c->lay.true_gates);
   xa.h = c->at<float>(c->lay.h);
   xa.y = c->at<float>(c->lay.y);
+  xa.out = c->at<float>(c->lay.y);
   xa.B = 1; xa.k = k; xa.H = H; xa.I = I;
   xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
   RouteArgs ra{};
@@ -674,6 +693,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   ra.gates_out = c->at<float>(c->lay.true_gates);
   ra.hit_counters = c->at<unsigned long long>(c->lay.hit_counters);
   ra.B = 1; ra.H = H; ra.E = E; ra.k = k; ra.eps = cfg.rms_eps; ra.bf16 = xa.bf16;
+  const bool fast = b1_supported(H, cfg.dtype);
   hipError_t le = hipSuccess;
   for (int pass = 0; pass < 2 && le == hipSuccess; ++pass) {      // pass 0 warms up
     const int n = pass == 0 ? std::min(reps, 4) : reps;
@@ -681,8 +701,8 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
     for (int i = 0; i < n && le == hipSuccess; ++i) {
       const int l = i % L;
       xa.pool = c->pool_base(l);
-      if (which == 0) le = launch_gateup(xa, act, cfg.dtype, c->compute);
-      else if (which == 1) le = launch_down(xa, act, cfg.dtype, c->compute);
+      if (which == 0) le = fast ? launch_gateup_b1(xa, act, cfg.dtype, c->compute) : launch_gateup(xa, act, cfg.dtype, c->compute);
+      else if (which == 1) le = fast ? launch_down_combine_b1(xa, act, cfg.dtype, c->compute) : launch_down(xa, act, cfg.dtype, c->compute);
       else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
     }
     if (pass == 1 && le == hipSuccess) le = hipEventRecord(t1, c->compute);

@@ -5,9 +5,11 @@
 // One launch covers the whole batch.  Every workgroup normalises the input rows itself (they
 // are a few KB and sit in L2), keeps them in LDS in double precision, and one wavefront per
 // router row streams that row once with 16-byte loads.  Logits go to global memory; the last
-// workgroup to arrive (a ticket counter, no waiting) sorts them in registers, one wavefront per
-// token, writes ids and gates, scores the previous prediction, and posts the ids to a pinned
+// workgroup to arrive (a ticket counter, no waiting) rank-sorts them in registers (keys stay in
+// VGPRs, broadcast lane by lane through scalar registers), writes ids and gates, scores the
+// previous prediction, and posts the ids to a pinned
 // host mailbox.  Everything that decides an expert index is double precision.
+// Layer order of the default-vector sum follows the id order (descending logit).
 #include "kernels.h"
 
 namespace moe_spec {
@@ -58,101 +60,95 @@ __device__ __forceinline__ double load_coherent(const double *p) {
   return __longlong_as_double(static_cast<long long>(u));
 }
 
-// (za, ia) ranks before (zb, ib): larger logit first, equal logits by lower index.
-__device__ __forceinline__ bool ranks_before(double za, int ia, double zb, int ib) {
-  return za > zb || (za == zb && ia < ib);
+// Broadcast of one lane's double through scalar registers.
+__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+  return __hiloint2double(hi, lo);
 }
 
-// Bitonic sort of 64*R (logit, index) pairs held R per lane, element i = lane*R + r, into rank
-// order.  Afterwards rank p sits in lane p / R, register p % R.
+// In-register rank sort of one token's logits.  Every wavefront holds all candidates in
+// registers (element i = r*64 + lane, R per lane) and counts, for each of its candidates, how
+// many candidates broadcast from source lanes [src_begin, src_end) rank before it: larger logit
+// first, equal logits by lower index.  The four wavefronts of the workgroup split the source
+// lanes and add their counts in LDS; a candidate's total is its position in the sorted order.
 template <int R>
-__device__ __forceinline__ void wave_rank_sort(double (&key)[R], int (&idx)[R], int lane) {
-  constexpr int N = kWave * R;
+__device__ __forceinline__ void rank_counts(const double (&key)[R], int lane, int src_begin, int src_end,
+                                            int (&cnt)[R]) {
 #pragma unroll
-  for (int k2 = 2; k2 <= N; k2 <<= 1) {
+  for (int r = 0; r < R; ++r) cnt[r] = 0;
+  for (int j = src_begin; j < src_end; ++j) {
 #pragma unroll
-    for (int j = k2 >> 1; j > 0; j >>= 1) {
-      if (j >= R) {
-        const int lj = j / R;
-        const bool lower = (lane & lj) == 0;
+    for (int r2 = 0; r2 < R; ++r2) {
+      const double zj = readlane_f64(key[r2], j);
+      const int ij = r2 * kWave + j;
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-          const int i = lane * R + r;
-          const double ok = __shfl_xor(key[r], lj);
-          const int oi = __shfl_xor(idx[r], lj);
-          const bool up = (i & k2) == 0;
-          const bool want_first = lower == up;
-          const bool other_first = ranks_before(ok, oi, key[r], idx[r]);
-          if (want_first == other_first) { key[r] = ok; idx[r] = oi; }
-        }
-      } else {
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-          if ((r & j) == 0) {
-            const int r2 = r | j;
-            const bool up = ((lane * R + r) & k2) == 0;
-            const bool second_first = ranks_before(key[r2], idx[r2], key[r], idx[r]);
-            if (second_first == up) {
-              const double tk = key[r]; key[r] = key[r2]; key[r2] = tk;
-              const int ti = idx[r]; idx[r] = idx[r2]; idx[r2] = ti;
-            }
-          }
-        }
-      }
+      for (int r = 0; r < R; ++r)
+        cnt[r] += (zj > key[r] || (zj == key[r] && ij < r * kWave + lane)) ? 1 : 0;
     }
   }
 }
 
-// Top-k, gates and bookkeeping for one token by one wavefront.
+struct FinishShared {
+  int rank[kMaxExperts];
+  double top_z[kMaxTopK];
+  int top_i[kMaxTopK];
+  int hits;
+};
+
+// Top-k, gates and bookkeeping of all tokens by the whole (last) workgroup, one token at a time.
 template <int R>
-__device__ void finish_token(const RouteArgs &a, int b, int lane) {
-  double key[R];
-  int idx[R];
+__device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
+  const int lane = tid & (kWave - 1), wave = tid / kWave;
+  constexpr int kSrcPerWave = kWave / (kRouteBlock / kWave);
+  if (tid == 0) sh.hits = 0;
+  for (int b = 0; b < a.B; ++b) {
+    double key[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int i = lane * R + r;
-    idx[r] = i;
-    key[r] = i < a.E ? load_coherent(a.z + size_t(b) * a.E + i) : -INFINITY;
-  }
-  wave_rank_sort<R>(key, idx, lane);
-
-  const double zmax = __shfl(key[0], 0);
-  double ex[R];
-  double part = 0.0;
+    for (int r = 0; r < R; ++r) {
+      const int i = r * kWave + lane;
+      key[r] = i < a.E ? load_coherent(a.z + size_t(b) * a.E + i) : -INFINITY;
+    }
+    for (int i = tid; i < kMaxExperts; i += kRouteBlock) sh.rank[i] = 0;
+    __syncthreads();
+    int cnt[R];
+    rank_counts<R>(key, lane, wave * kSrcPerWave, (wave + 1) * kSrcPerWave, cnt);
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int p = lane * R + r;
-    ex[r] = p < a.k ? exp(key[r] - zmax) : 0.0;
-    part += ex[r];
-  }
-  const double denom = wave_sum(part);
-
-  int my_hits = 0;
+    for (int r = 0; r < R; ++r) atomicAdd(&sh.rank[r * kWave + lane], cnt[r]);
+    __syncthreads();
+    if (wave == 0) {
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int p = lane * R + r;
-    if (p < a.k) {
-      const double g = ex[r] / denom;
-      const size_t o = size_t(b) * a.k + p;
-      a.ids_out[o] = idx[r];
+      for (int r = 0; r < R; ++r) {
+        const int i = r * kWave + lane;
+        const int rk = sh.rank[i];
+        if (i < a.E && rk < a.k) { sh.top_z[rk] = key[r]; sh.top_i[rk] = i; }
+      }
+    }
+    __syncthreads();
+    if (tid < a.k) {
+      const double zmax = sh.top_z[0];
+      double denom = 0.0;
+      for (int q = 0; q < a.k; ++q) denom += exp(sh.top_z[q] - zmax);
+      const double g = exp(sh.top_z[tid] - zmax) / denom;
+      const int id = sh.top_i[tid];
+      const size_t o = size_t(b) * a.k + tid;
+      a.ids_out[o] = id;
       a.gates_out[o] = static_cast<float>(g);
       if (a.gates64_out) a.gates64_out[o] = g;
-      if (a.user_ids) a.user_ids[o] = idx[r];
+      if (a.user_ids) a.user_ids[o] = id;
       if (a.user_gates) a.user_gates[o] = static_cast<float>(g);
-      if (a.mailbox) a.mailbox->ids[o] = idx[r];
+      if (a.mailbox) a.mailbox->ids[o] = id;
       if (a.cmp_ids) {
-        for (int j = 0; j < a.k; ++j) my_hits += (a.cmp_ids[size_t(b) * a.k + j] == idx[r]);
+        int hit = 0;
+        for (int j = 0; j < a.k; ++j) hit |= (a.cmp_ids[size_t(b) * a.k + j] == id);
+        if (hit) atomicAdd(&sh.hits, 1);
       }
     }
+    __syncthreads();
   }
-  if (a.cmp_ids) {
-    int h = my_hits;
-#pragma unroll
-    for (int m = 32; m > 0; m >>= 1) h += __shfl_xor(h, m);
-    if (lane == 0) {
-      atomicAdd(&a.hit_counters[0], static_cast<unsigned long long>(h));
-      atomicAdd(&a.hit_counters[1], static_cast<unsigned long long>(a.k));
-    }
+  if (tid == 0 && a.cmp_ids) {
+    atomicAdd(&a.hit_counters[0], static_cast<unsigned long long>(sh.hits));
+    atomicAdd(&a.hit_counters[1], static_cast<unsigned long long>(a.k) * a.B);
   }
 }
 
@@ -161,6 +157,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   extern __shared__ double vec[];            // [tok_tile][H]
   __shared__ double red[kRouteBlock / kWave];
   __shared__ int last_flag;
+  __shared__ FinishShared fin;
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int row = blockIdx.x * kRouteRowsPerBlock + wave;
@@ -175,21 +172,31 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
       const int b = b0 + t;
       double *v = vec + size_t(t) * H;
       double ss = 0.0;
-      for (int i = tid; i < H; i += kRouteBlock) {
-        double u;
+      for (int c = tid * VN; c < H; c += kRouteBlock * VN) {     // VN consecutive elements per thread
+        double u[VN];
+        const float *base = (a.spec && a.from_normalized ? a.s_in : a.r) + size_t(b) * H + c;
+#pragma unroll
+        for (int x = 0; x < VN; x += 4) {
+          const float4 f = *reinterpret_cast<const float4 *>(base + x);
+          u[x] = f.x; u[x + 1] = f.y; u[x + 2] = f.z; u[x + 3] = f.w;
+        }
         if (a.spec) {
-          u = a.from_normalized ? double(a.s_in[size_t(b) * H + i]) : double(a.r[size_t(b) * H + i]);
-          double d = 0.0;
+          double d[VN];
+#pragma unroll
+          for (int x = 0; x < VN; ++x) d[x] = 0.0;
           for (int j = 0; j < a.k; ++j) {
             const int e = a.d_ids[b * a.k + j];
-            d += a.d_gates[b * a.k + j] * double(Chunk<WT>::one(dv + size_t(e) * H + i));
+            const double g = a.d_gates[b * a.k + j];
+            float dvf[VN];
+            Chunk<WT>::load(dv + size_t(e) * H + c, dvf);
+#pragma unroll
+            for (int x = 0; x < VN; ++x) d[x] += g * double(dvf[x]);
           }
-          u += d;
-        } else {
-          u = double(a.r[size_t(b) * H + i]);
+#pragma unroll
+          for (int x = 0; x < VN; ++x) u[x] += d[x];
         }
-        v[i] = u;
-        ss += u * u;
+#pragma unroll
+        for (int x = 0; x < VN; ++x) { v[c + x] = u[x]; ss += u[x] * u[x]; }
       }
       ss = wave_sum(ss);
       __syncthreads();                       // red[] free again
@@ -247,12 +254,10 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   if (!last_flag) return;
   __threadfence();
 
-  for (int b = wave; b < a.B; b += kRouteBlock / kWave) {
-    if (a.E <= kWave) finish_token<1>(a, b, lane);
-    else if (a.E <= 2 * kWave) finish_token<2>(a, b, lane);
-    else finish_token<4>(a, b, lane);
-  }
-  __threadfence_system();
+  if (a.E <= kWave) finish_tokens<1>(a, fin, tid);
+  else if (a.E <= 2 * kWave) finish_tokens<2>(a, fin, tid);
+  else finish_tokens<4>(a, fin, tid);
+  if (a.mailbox) __threadfence_system();
   __syncthreads();
   if (tid == 0) {
     *a.counter = 0u;
