@@ -9,6 +9,8 @@
 // Weights are read once per token tile; at batch 1 that is exactly once.
 #include "kernels.h"
 
+#include <cstdlib>
+
 namespace moe_spec {
 namespace {
 
@@ -424,7 +426,8 @@ hipError_t launch_down_t(const ExpertArgs &a, const ActiveList &act, hipStream_t
 template <typename WT, int NCH>
 void launch_gateup_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
   // one row per wavefront until that would exceed about 6144 wavefronts (24 per compute unit)
-  long rpw = (long(a.I) * act.n + 6143) / 6144;
+  static const long target = getenv("MOE_SPEC_GU_WAVES") ? atol(getenv("MOE_SPEC_GU_WAVES")) : 6144;
+  long rpw = (long(a.I) * act.n + target - 1) / target;
   if (rpw < 1) rpw = 1;
   const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
   hipLaunchKernelGGL((gateup_b1_kernel<WT, NCH>), grid, block, 0, st, a, act, int(rpw));

@@ -384,7 +384,8 @@ int moe_spec_set_layer_resident(moe_spec_ctx *c, int layer, const void *router_w
   if (!c) return MOE_SPEC_EINVAL;
   if (layer < 0 || layer >= c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
   if (!router_w || !rms_gain || !default_vecs) return c->fail(MOE_SPEC_EINVAL, "null table pointer");
-  if ((reinterpret_cast<uintptr_t>(router_w) | reinterpret_cast<uintptr_t>(default_vecs)) & 15)
+  if ((reinterpret_cast<uintptr_t>(router_w) | reinterpret_cast<uintptr_t>(default_vecs) |
+       reinterpret_cast<uintptr_t>(rms_gain)) & 15)
     return c->fail(MOE_SPEC_EINVAL, "tables must be 16-byte aligned");
   c->router_w[layer] = router_w;
   c->gain[layer] = rms_gain;

@@ -18,10 +18,27 @@ namespace {
 constexpr int kWave = 64;
 constexpr int kMaxTokTile = 4;
 
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+  return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes, the same value in every lane: quad permutes and mirrors inside each
+// row of 16 lanes, then one lane of each row through scalar registers.
 __device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);
-  return v;
+  v += dpp_move_f64<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move_f64<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move_f64<0x141>(v);   // row_half_mirror
+  v += dpp_move_f64<0x140>(v);   // row_mirror
+  return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
 }
 
 // Nearest bfloat16 (8 significant bits), ties to even, straight from the double.
@@ -35,7 +52,14 @@ __device__ __forceinline__ double round_to_bf16(double x) {
 // 16 bytes of weights -> floats.  bf16: 8 values, float: 4 values.
 template <typename WT> struct Chunk;
 template <> struct Chunk<uint16_t> {
+  using Raw = uint4;
   static constexpr int N = 8;
+  __device__ static void unpack(const uint4 &v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
   __device__ static void load(const uint16_t *p, float (&f)[8]) {
     const uint4 v = *reinterpret_cast<const uint4 *>(p);
     f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
@@ -46,7 +70,9 @@ template <> struct Chunk<uint16_t> {
   __device__ static float one(const uint16_t *p) { return __uint_as_float(uint32_t(*p) << 16); }
 };
 template <> struct Chunk<float> {
+  using Raw = float4;
   static constexpr int N = 4;
+  __device__ static void unpack(const float4 &v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
   __device__ static void load(const float *p, float (&f)[4]) {
     const float4 v = *reinterpret_cast<const float4 *>(p);
     f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
@@ -58,13 +84,6 @@ __device__ __forceinline__ double load_coherent(const double *p) {
   const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   return __longlong_as_double(static_cast<long long>(u));
-}
-
-// Broadcast of one lane's double through scalar registers.
-__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
-  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
-  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
-  return __hiloint2double(hi, lo);
 }
 
 // In-register rank sort of one token's logits.  Every wavefront holds all candidates in
@@ -92,6 +111,7 @@ __device__ __forceinline__ void rank_counts(const double (&key)[R], int lane, in
 struct FinishShared {
   int rank[kMaxExperts];
   double top_z[kMaxTopK];
+  double top_e[kMaxTopK];
   int top_i[kMaxTopK];
   int hits;
 };
@@ -125,11 +145,16 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
       }
     }
     __syncthreads();
+    double my_exp = 0.0;
     if (tid < a.k) {
-      const double zmax = sh.top_z[0];
+      my_exp = exp(sh.top_z[tid] - sh.top_z[0]);
+      sh.top_e[tid] = my_exp;
+    }
+    __syncthreads();
+    if (tid < a.k) {
       double denom = 0.0;
-      for (int q = 0; q < a.k; ++q) denom += exp(sh.top_z[q] - zmax);
-      const double g = exp(sh.top_z[tid] - zmax) / denom;
+      for (int q = 0; q < a.k; ++q) denom += sh.top_e[q];
+      const double g = my_exp / denom;
       const int id = sh.top_i[tid];
       const size_t o = size_t(b) * a.k + tid;
       a.ids_out[o] = id;
@@ -152,7 +177,10 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
   }
 }
 
-template <typename WT>
+// NCH > 0: the wavefront's router row (NCH 16-byte chunks per lane) is loaded into registers at
+// the top of the kernel, so its HBM latency overlaps the normalisation; NCH = 0 streams the row
+// in a loop for hidden sizes beyond 64*8 chunks.
+template <typename WT, int NCH>
 __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   extern __shared__ double vec[];            // [tok_tile][H]
   __shared__ double red[kRouteBlock / kWave];
@@ -165,6 +193,17 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   const WT *dv = static_cast<const WT *>(a.dvec);
   const int H = a.H;
   constexpr int VN = Chunk<WT>::N;
+  using Raw = typename Chunk<WT>::Raw;
+
+  constexpr int NREG = NCH > 0 ? NCH : 1;
+  Raw wreg[NREG];
+  if (NCH > 0 && row < a.E) {
+#pragma unroll
+    for (int ch = 0; ch < NREG; ++ch) {
+      const int c = (ch * kWave + lane) * VN;
+      wreg[ch] = *reinterpret_cast<const Raw *>(w + size_t(row) * H + (c < H ? c : 0));
+    }
+  }
 
   for (int b0 = 0; b0 < a.B; b0 += a.tok_tile) {
     const int nb = min(a.tok_tile, a.B - b0);
@@ -184,19 +223,34 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
           double d[VN];
 #pragma unroll
           for (int x = 0; x < VN; ++x) d[x] = 0.0;
-          for (int j = 0; j < a.k; ++j) {
-            const int e = a.d_ids[b * a.k + j];
-            const double g = a.d_gates[b * a.k + j];
-            float dvf[VN];
-            Chunk<WT>::load(dv + size_t(e) * H + c, dvf);
+          for (int j0 = 0; j0 < a.k; j0 += 4) {            // four default-vector rows in flight
+            Raw dr[4];
+            double g[4];
 #pragma unroll
-            for (int x = 0; x < VN; ++x) d[x] += g * double(dvf[x]);
+            for (int q = 0; q < 4; ++q) {
+              const int j = min(j0 + q, a.k - 1);
+              g[q] = j0 + q < a.k ? a.d_gates[b * a.k + j] : 0.0;
+              dr[q] = *reinterpret_cast<const Raw *>(dv + size_t(a.d_ids[b * a.k + j]) * H + c);
+            }
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              float dvf[VN];
+              Chunk<WT>::unpack(dr[q], dvf);
+#pragma unroll
+              for (int x = 0; x < VN; ++x) d[x] += g[q] * double(dvf[x]);
+            }
           }
 #pragma unroll
           for (int x = 0; x < VN; ++x) u[x] += d[x];
         }
+        float gf[VN];                                    // gains now, so that no load follows the reduction
 #pragma unroll
-        for (int x = 0; x < VN; ++x) { v[c + x] = u[x]; ss += u[x] * u[x]; }
+        for (int x = 0; x < VN; x += 4) {
+          const float4 f = *reinterpret_cast<const float4 *>(a.gain + c + x);
+          gf[x] = f.x; gf[x + 1] = f.y; gf[x + 2] = f.z; gf[x + 3] = f.w;
+        }
+#pragma unroll
+        for (int x = 0; x < VN; ++x) { v[c + x] = u[x] * double(gf[x]); ss += u[x] * u[x]; }
       }
       ss = wave_sum(ss);
       __syncthreads();                       // red[] free again
@@ -207,7 +261,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
       for (int x = 0; x < kRouteBlock / kWave; ++x) tot += red[x];
       const double root = sqrt(tot / double(H) + double(a.eps));
       for (int i = tid; i < H; i += kRouteBlock) {
-        double n = v[i] * double(a.gain[i]) / root;
+        double n = v[i] / root;                          // v holds x*gain
         if (a.bf16) n = round_to_bf16(n);
         v[i] = n;
         if (blockIdx.x == 0 && a.vec_out) a.vec_out[size_t(b) * H + i] = static_cast<float>(n);
@@ -219,16 +273,47 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
       double acc[kMaxTokTile];
 #pragma unroll
       for (int t = 0; t < kMaxTokTile; ++t) acc[t] = 0.0;
-      const WT *wr = w + size_t(row) * H;
-      for (int c = lane * VN; c < H; c += kWave * VN) {
-        float wf[VN];
-        Chunk<WT>::load(wr + c, wf);
+      if (NCH > 0) {
 #pragma unroll
-        for (int t = 0; t < kMaxTokTile; ++t) {
-          if (t < nb) {
-            const double *v = vec + size_t(t) * H + c;
+        for (int ch = 0; ch < NREG; ++ch) {
+          const int c = (ch * kWave + lane) * VN;
+          if (c < H) {
+            float wf[VN];
+            Chunk<WT>::unpack(wreg[ch], wf);
 #pragma unroll
-            for (int x = 0; x < VN; ++x) acc[t] += double(wf[x]) * v[x];
+            for (int t = 0; t < kMaxTokTile; ++t) {
+              if (t < nb) {
+                const double *v = vec + size_t(t) * H + c;
+#pragma unroll
+                for (int x = 0; x < VN; ++x) acc[t] += double(wf[x]) * v[x];
+              }
+            }
+          }
+        }
+      } else {
+        const WT *wr = w + size_t(row) * H;
+        for (int c0 = lane * VN; c0 < H; c0 += 4 * kWave * VN) {     // four chunks in flight
+          Raw wr4[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * kWave * VN;
+            wr4[u] = *reinterpret_cast<const Raw *>(wr + (c < H ? c : 0));
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * kWave * VN;
+            if (c < H) {
+              float wf[VN];
+              Chunk<WT>::unpack(wr4[u], wf);
+#pragma unroll
+              for (int t = 0; t < kMaxTokTile; ++t) {
+                if (t < nb) {
+                  const double *v = vec + size_t(t) * H + c;
+#pragma unroll
+                  for (int x = 0; x < VN; ++x) acc[t] += double(wf[x]) * v[x];
+                }
+              }
+            }
           }
         }
       }
@@ -277,23 +362,37 @@ size_t route_lds_bytes(int H, int B, int *tok_tile) {
   return size_t(tt) * H * sizeof(double);
 }
 
-hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st) {
-  RouteArgs args = a;
-  const size_t lds = route_lds_bytes(a.H, a.B, &args.tok_tile);
-  const dim3 grid((a.E + kRouteRowsPerBlock - 1) / kRouteRowsPerBlock), block(kRouteBlock);
-  if (dtype == 1)
-    hipLaunchKernelGGL(route_kernel<uint16_t>, grid, block, lds, st, args);
-  else
-    hipLaunchKernelGGL(route_kernel<float>, grid, block, lds, st, args);
+template <typename WT, int NCH>
+hipError_t launch_route_n(const RouteArgs &args, size_t lds, hipStream_t st) {
+  static bool big_lds_allowed = false;       // dynamic LDS above the 64 KB default is opt-in
+  if (!big_lds_allowed) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(route_kernel<WT, NCH>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 << 10);
+    if (e != hipSuccess) return e;
+    big_lds_allowed = true;
+  }
+  const dim3 grid((args.E + kRouteRowsPerBlock - 1) / kRouteRowsPerBlock), block(kRouteBlock);
+  hipLaunchKernelGGL((route_kernel<WT, NCH>), grid, block, lds, st, args);
   return hipGetLastError();
 }
 
-hipError_t init_route_kernels() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(route_kernel<uint16_t>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 96 << 10);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void *>(route_kernel<float>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 96 << 10);
+template <typename WT>
+hipError_t launch_route_t(const RouteArgs &args, size_t lds, hipStream_t st) {
+  const int need = (args.H + kWave * Chunk<WT>::N - 1) / (kWave * Chunk<WT>::N);
+  if (need <= 1) return launch_route_n<WT, 1>(args, lds, st);
+  if (need <= 2) return launch_route_n<WT, 2>(args, lds, st);
+  if (need <= 4) return launch_route_n<WT, 4>(args, lds, st);
+  if (need <= 6) return launch_route_n<WT, 6>(args, lds, st);
+  if (need <= 8) return launch_route_n<WT, 8>(args, lds, st);
+  return launch_route_n<WT, 0>(args, lds, st);
 }
+
+hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st) {
+  RouteArgs args = a;
+  const size_t lds = route_lds_bytes(a.H, a.B, &args.tok_tile);
+  return dtype == 1 ? launch_route_t<uint16_t>(args, lds, st) : launch_route_t<float>(args, lds, st);
+}
+
+hipError_t init_route_kernels() { return hipSuccess; }
 
 }  // namespace moe_spec

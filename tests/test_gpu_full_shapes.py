@@ -1,0 +1,46 @@
+"""GPU parity at the full layer shapes of the benchmark workloads (hidden size, experts, top-k,
+intermediate size, batch, slots per layer: the launch configuration bench.py times), on a few
+layers and tokens so that the CPU checker finishes in seconds.  The expert pool is drawn on the
+GPU and copied to pinned memory; the checker reads those same bytes."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2603_19289_amd import workload as W
+from tests.helpers import oracle_model
+from tests.test_gpu_parity import MODES, run_teacher_forced
+
+pytestmark = pytest.mark.gpu
+
+
+def prebuilt(wl):
+    res = W.make_resident(wl)
+    tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+    pool = torch.empty((wl.n_layers, wl.n_experts, wl.expert_elems), dtype=tdtype, pin_memory=True)
+    W.fill_experts_gpu(wl, pool)
+    pool_np = pool.view(torch.int16).numpy().view(np.uint16) if wl.dtype == "bf16" else pool.numpy()
+    return res, oracle_model(wl, res, pool_np), pool
+
+
+CASES = {
+    "c2_qwen3_30b_a3b": dict(n_layers=3, tokens=3),
+    "c3_gpt_oss_20b": dict(n_layers=3, tokens=2),
+    "c3_gpt_oss_20b_b8": dict(n_layers=2, tokens=1),
+    "c4_mixtral_8x7b": dict(n_layers=2, tokens=2),
+    "c5_qwen3_b32": dict(n_layers=2, tokens=1),
+}
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_full_layer_shape_both_modes(name):
+    wl = W.CONFIGS[name].with_(**CASES[name])
+    pre = prebuilt(wl)
+    for mode in MODES:
+        run_teacher_forced(wl, MODES[mode], prebuilt=pre)
+
+
+def test_full_layer_shape_with_dma_copy_engine():
+    from paper_2603_19289_amd import moe_spec as M
+    wl = W.CONFIGS["c2_qwen3_30b_a3b"].with_(n_layers=2, tokens=2)
+    run_teacher_forced(wl, O.MODE_SPECULATIVE, prebuilt=prebuilt(wl), copy_engine=M.COPY_DMA)

@@ -19,16 +19,20 @@ def rel_err(got, want):
     return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
 
 
-def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label=""):
-    """The checker runs free; the GPU step is fed the checker's r_l at every layer."""
+def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", prebuilt=None, **engine_kw):
+    """The checker runs free; the GPU step is fed the checker's r_l at every layer.
+    prebuilt = (resident tables, checker model, pinned torch pool) for pools drawn on the GPU."""
     from paper_2603_19289_amd.engine import engine_for
     print(f"[case] {label or wl.name} mode={mode} L={wl.n_layers} H={wl.hidden} E={wl.n_experts} k={wl.top_k} "
           f"I={wl.inter} B={wl.batch} S={wl.slots} {wl.dtype}", flush=True)
-    res, ex, model = build(wl, gains)
+    if prebuilt is None:
+        res, ex, model = build(wl, gains)
+    else:
+        res, model, ex = prebuilt
     x0, eps = W.make_inputs(wl)
     orc = O.MoEOracle(model, mode, wl.slots, q_from_normalized=bool(q_from_normalized))
     trace = O.run_tokens(orc, x0, make_advance(wl, eps))
-    eng = engine_for(wl, mode, res, ex, q_from_normalized=q_from_normalized)
+    eng = engine_for(wl, mode, res, ex, q_from_normalized=q_from_normalized, **engine_kw)
     worst = 0.0
     try:
         for t in range(wl.tokens):
