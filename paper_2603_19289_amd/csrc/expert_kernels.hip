@@ -342,6 +342,108 @@ __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArg
   if (lane == 0) a.out[row] = v;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Matrix-core kernels for decode batches of 16 and more (bf16 weights): with that many tokens
+// the vector ALUs, not HBM, would limit a GEMV, so the expert FFN is done as 16x16x32 bf16 MFMA
+// tiles.  A operand = 16 weight rows, B operand = up to 16 tokens routed to the expert, K walks
+// the reduction dimension 64 columns per step: lane (m, g) = (lane % 16, lane / 16) loads the 32
+// contiguous bytes at column k0 + 16 g of row m (so four lanes cover one 128-byte line) and
+// feeds the first 8 columns to one MFMA and the next 8 to a second one; the B operand is read
+// with the same column assignment, which is all that the contraction needs.
+// Accumulator layout: lane holds token column lane % 16, rows 4 (lane / 16) .. +3.
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+__device__ __forceinline__ bf16x8_t load_bf16x8(const uint16_t *p, bool valid) {
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (valid) v = *reinterpret_cast<const uint4 *>(p);
+  return __builtin_bit_cast(bf16x8_t, v);
+}
+
+// GATEUP: hq[f, row] = bf16(silu(W_gate[row,:] . s_b) * (W_up[row,:] . s_b)),  act_q = s_l as bf16 [B, K]
+// else  : y[f, row]  = W_down[row,:] . hq[f,:],                                  act_q = hq [B*k, K]
+template <bool GATEUP, int NT>
+__global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a, const ActiveList act,
+                                                             const uint16_t *act_q, uint16_t *hq_out) {
+  __shared__ int list[kMaxBatch];
+  __shared__ int n_list;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int m = lane & 15, g = lane >> 4;
+  const int K = GATEUP ? a.H : a.I;            // reduction length
+  const int R = GATEUP ? a.I : a.H;            // output rows
+
+  const int e = act.expert[blockIdx.y];
+  const uint16_t *wbase = reinterpret_cast<const uint16_t *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
+  gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
+  const int n = n_list;
+  const int row_base = (blockIdx.x * kWaves + wave) * 16;
+  if (row_base >= R || n == 0) return;
+  const int ntiles = (n + 15) / 16;
+  const int my_row = min(row_base + m, R - 1);
+  const uint16_t *p0 = wbase + (GATEUP ? size_t(0) : size_t(2) * a.I * a.H) + size_t(my_row) * K;
+  const uint16_t *p1 = p0 + size_t(a.I) * a.H;             // W_up row (GATEUP only)
+
+  const uint16_t *bp[NT];
+  bool bvalid[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    const int idx = t * 16 + m;
+    bvalid[t] = idx < n;
+    const int f = bvalid[t] ? list[idx] : 0;
+    bp[t] = act_q + size_t(GATEUP ? f / a.k : f) * K;
+  }
+  f32x4_t acc0[NT], acc1[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) { acc0[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; acc1[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
+
+  for (int k0 = 0; k0 < K; k0 += 64) {
+    const int kk = k0 + 16 * g;
+    const bool v0 = kk < K, v1 = kk + 8 < K;
+    const bf16x8_t a00 = load_bf16x8(p0 + kk, v0), a01 = load_bf16x8(p0 + kk + 8, v1);
+    bf16x8_t a10 = a00, a11 = a01;
+    if (GATEUP) { a10 = load_bf16x8(p1 + kk, v0); a11 = load_bf16x8(p1 + kk + 8, v1); }
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (t < ntiles) {
+        const bf16x8_t b0 = load_bf16x8(bp[t] + kk, v0 && bvalid[t]);
+        const bf16x8_t b1 = load_bf16x8(bp[t] + kk + 8, v1 && bvalid[t]);
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a00, b0, acc0[t], 0, 0, 0);
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01, b1, acc0[t], 0, 0, 0);
+        if (GATEUP) {
+          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a10, b0, acc1[t], 0, 0, 0);
+          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a11, b1, acc1[t], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  const int r0 = row_base + 4 * g;             // this lane's four output rows, all inside or all outside
+  if (r0 >= R) return;
+#pragma unroll
+  for (int t = 0; t < NT; ++t) {
+    if (t < ntiles && bvalid[t]) {
+      const int f = list[t * 16 + m];
+      if (GATEUP) {
+        uint16_t q[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float gv = acc0[t][i], uv = acc1[t][i];
+          const float hv = round_to_bf16(gv / (1.f + expf(-gv)) * uv);
+          q[i] = uint16_t(__float_as_uint(hv) >> 16);
+        }
+        uint2 packed;
+        packed.x = uint32_t(q[0]) | (uint32_t(q[1]) << 16);
+        packed.y = uint32_t(q[2]) | (uint32_t(q[3]) << 16);
+        *reinterpret_cast<uint2 *>(hq_out + size_t(f) * R + r0) = packed;
+      } else {
+        *reinterpret_cast<float4 *>(a.y + size_t(f) * R + r0) =
+            make_float4(acc0[t][0], acc0[t][1], acc0[t][2], acc0[t][3]);
+      }
+    }
+  }
+}
+
 // O[b, i] = sum_j gates[b, j] * y[b, j, i]
 __global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
   const int i = blockIdx.x * kBlock + threadIdx.x;
@@ -455,6 +557,21 @@ void launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, hipStrea
   hipLaunchKernelGGL((down_combine_b1_kernel<WT>), grid, block, 0, st, a, act, inv_chunks);
 }
 
+template <bool GATEUP>
+hipError_t launch_expert_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *act_q, uint16_t *hq,
+                              hipStream_t st) {
+  const int rows = GATEUP ? a.I : a.H;
+  const dim3 grid((rows + 16 * kWaves - 1) / (16 * kWaves), act.n), block(kBlock);
+  const int nt = (a.B + 15) / 16;
+  switch (nt) {
+    case 1: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 1>), grid, block, 0, st, a, act, act_q, hq); break;
+    case 2: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 2>), grid, block, 0, st, a, act, act_q, hq); break;
+    case 3: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 3>), grid, block, 0, st, a, act, act_q, hq); break;
+    default: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 4>), grid, block, 0, st, a, act, act_q, hq); break;
+  }
+  return hipGetLastError();
+}
+
 template <typename K>
 hipError_t allow_big_lds(K kernel) {
   return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
@@ -487,6 +604,19 @@ hipError_t launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, in
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st) {
   if (act.n <= 0) return hipSuccess;
   return dtype == 1 ? launch_down_t<uint16_t>(a, act, st) : launch_down_t<float>(a, act, st);
+}
+
+// bf16 weights, batch >= 16: s_q is s_l as bf16 [B,H]; hq (bf16 [B,k,I]) is written by the gate/up
+// launch and read by the down launch.
+hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
+                              hipStream_t st) {
+  if (act.n <= 0) return hipSuccess;
+  return launch_expert_mfma<true>(a, act, s_q, hq, st);
+}
+
+hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st) {
+  if (act.n <= 0) return hipSuccess;
+  return launch_expert_mfma<false>(a, act, hq, nullptr, st);
 }
 
 hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st) {

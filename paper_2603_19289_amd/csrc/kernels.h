@@ -34,6 +34,7 @@ struct RouteArgs {
   double *z;                  // [B,E] logits scratch
   unsigned int *counter;      // arrival counter, zero between launches
   float *vec_out;             // [B,H] normalised (and rounded) vector, or null
+  uint16_t *vec_out_q;        // [B,H] the same as bf16 bit patterns (bf16 mode), or null
   int32_t *ids_out;           // [B,k]
   float *gates_out;           // [B,k]
   double *gates64_out;        // [B,k] or null
@@ -82,6 +83,10 @@ hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_combine(const ExpertArgs &a, hipStream_t st);
+hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
+                              hipStream_t st);
+hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);
+constexpr int kMfmaMinBatch = 16;     // decode batches from here on use the matrix-core expert kernels
 bool b1_supported(int H, int dtype);
 hipError_t launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);

@@ -42,7 +42,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      hit_counters, h, y, bench_ids, total;
+      hit_counters, h, y, bench_ids, s_q, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -85,6 +85,7 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.h = take(B * k * I * 4);
   a.y = take(B * k * H * 4);
   a.bench_ids = take(256);
+  a.s_q = take(B * H * 2);
   a.total = off;
   return a;
 }
@@ -465,6 +466,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   ra.z = c->at<double>(c->lay.z);
   ra.counter = c->at<unsigned int>(c->lay.counter);
   ra.vec_out = c->at<float>(c->lay.s_buf);
+  ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch ? c->at<uint16_t>(c->lay.s_q) : nullptr;
   ra.ids_out = c->at<int32_t>(c->lay.true_ids);
   ra.gates_out = c->at<float>(c->lay.true_gates);
   ra.gates64_out = c->at<double>(c->lay.true_gates64);
@@ -493,6 +495,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     pa.d_ids = c->at<int32_t>(c->lay.true_ids);
     pa.d_gates = c->at<double>(c->lay.true_gates64);
     pa.vec_out = nullptr;
+    pa.vec_out_q = nullptr;
     pa.ids_out = c->at<int32_t>(c->lay.pend_ids[(layer + 1) & 1]);
     pa.gates_out = c->at<float>(c->lay.pend_gates[(layer + 1) & 1]);
     pa.gates64_out = nullptr;
@@ -548,6 +551,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
 
   const bool fast_b1 = batch == 1 && b1_supported(H, cfg.dtype);
+  const bool use_mfma = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch;
 
   // --- cache waves: make resident (unless prefetched), wait, run
   TimedSpan *sp_stall = c->open_span(2, c->compute);
@@ -579,6 +583,11 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
       }
       if ((e = launch_gateup_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
       if ((e = launch_down_combine_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+    } else if (use_mfma) {
+      uint16_t *hq = c->at<uint16_t>(c->lay.h);
+      if ((e = launch_gateup_mfma(xa, act, c->at<uint16_t>(c->lay.s_q), hq, c->compute)) != hipSuccess)
+        return c->hip_fail(e, "gate/up MFMA kernel");
+      if ((e = launch_down_mfma(xa, act, hq, c->compute)) != hipSuccess) return c->hip_fail(e, "down MFMA kernel");
     } else {
       if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
       if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");

@@ -265,6 +265,8 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
         if (a.bf16) n = round_to_bf16(n);
         v[i] = n;
         if (blockIdx.x == 0 && a.vec_out) a.vec_out[size_t(b) * H + i] = static_cast<float>(n);
+        if (blockIdx.x == 0 && a.vec_out_q)
+          a.vec_out_q[size_t(b) * H + i] = uint16_t(__float_as_uint(static_cast<float>(n)) >> 16);
       }
     }
     __syncthreads();

@@ -96,6 +96,16 @@ def test_batches_and_cache_waves(mode, B, S):
 
 
 @pytest.mark.parametrize("mode", list(MODES))
+@pytest.mark.parametrize("B,S", [(16, 12), (23, 5), (40, 4), (64, 7)])
+def test_matrix_core_path_batches_of_16_and_more(mode, B, S):
+    # bf16 and B >= 16 runs the MFMA expert kernels: ragged K tail (264 = 4*64 + 8), ragged row
+    # tiles (200 = 12*16 + 8), more than 16 tokens per expert, several cache waves
+    wl = small_workload(name="mfma", n_layers=3, hidden=264, n_experts=12, top_k=3, inter=200,
+                        dtype="bf16", batch=B, tokens=2, slots=S, seed=13)
+    run_teacher_forced(wl, MODES[mode])
+
+
+@pytest.mark.parametrize("mode", list(MODES))
 def test_edge_shapes(mode):
     # every expert selected; pool exactly k; one expert; one layer (no prediction at all)
     run_teacher_forced(small_workload(name="all_experts", n_experts=4, top_k=4, slots=4, tokens=3, dtype="f32"), MODES[mode])
