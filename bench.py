@@ -34,7 +34,9 @@ def parse():
     p.add_argument("--reps", type=int, default=3, help="interleaved A/B repetitions")
     p.add_argument("--workload", default="c2_qwen3_30b_a3b")
     p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
-    p.add_argument("--cpu-tokens", type=int, default=2, help="tokens the CPU checker is timed on (0 = skip)")
+    p.add_argument("--cpu-tokens", type=int, default=4, help="tokens the CPU checker is timed on (0 = skip)")
+    p.add_argument("--calibrate-copy", action="store_true",
+                   help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
     p.add_argument("--kernel-reps", type=int, default=480)
     p.add_argument("--copy-engine", choices=["kernel", "dma"], default="kernel")
     return p.parse_args()
@@ -155,9 +157,16 @@ def main():
         kern[name] = {"ms_per_launch": ms, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
     prof_eng.close()
     dom = kern["expert_gateup_gemv"]
-    roofline = {"bound": "hbm", "kernel": "gateup_kernel (expert W_gate/W_up GEMV + SwiGLU)", "achieved": dom["gbs"],
+    roofline = {"bound": "hbm", "kernel": "gateup_b1_kernel (expert W_gate/W_up GEMV + SwiGLU, batch 1)", "achieved": dom["gbs"],
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None,
                 "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"}}
+
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        log("[bench] calibration copy: 268435456 bytes read + 268435456 bytes written in one dispatch")
 
     # ---- the CPU checker timed on this host, on a bounded prefix of the same workload
     cpu = None

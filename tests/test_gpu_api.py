@@ -1,0 +1,158 @@
+"""GPU-side checks of the C ABI's state machine and error returns, of reset/repeatability, of the
+two copy engines agreeing, and free-running parity with a margin audit."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2603_19289_amd import moe_spec as M
+from paper_2603_19289_amd import workload as W
+from tests.helpers import build, make_advance, small_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _engine(wl, mode, res, ex, **kw):
+    from paper_2603_19289_amd.engine import engine_for
+    return engine_for(wl, mode, res, ex, **kw)
+
+
+def test_state_machine_errors():
+    wl = small_workload(n_layers=3, tokens=1)
+    res, ex, _ = build(wl)
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex)
+    r = torch.randn(1, wl.hidden, device="cuda")
+    out = torch.empty_like(r)
+    lib = M.lib()
+    step = lambda layer, batch=1: lib.moe_spec_layer_step(eng.ctx, layer, r.data_ptr(), batch, out.data_ptr(), None)
+    assert step(0) == M.ESTATE                                   # before begin_token
+    assert b"begin_token" in lib.moe_spec_last_error(eng.ctx)
+    eng.begin_token()
+    assert step(1) == M.ESTATE                                   # out of order
+    assert step(0, batch=2) == M.EINVAL                          # beyond max_batch
+    assert lib.moe_spec_layer_step(eng.ctx, 0, None, 1, out.data_ptr(), None) == M.EINVAL
+    assert step(0) == M.OK
+    assert step(0) == M.ESTATE                                   # layer 0 twice
+    assert step(1) == M.OK and step(2) == M.OK
+    assert step(3) == M.ESTATE                                   # past the last layer: token is closed
+    torch.cuda.synchronize()
+    # registration errors
+    assert lib.moe_spec_set_layer_resident(eng.ctx, 9, 1, 1, 1) == M.EINVAL
+    assert lib.moe_spec_load_host_experts(eng.ctx, 0, 0, wl.n_experts + 1, eng.pool.data_ptr(), 0) == M.EINVAL
+    assert lib.moe_spec_load_host_experts(eng.ctx, 0, 0, 1, eng.pool.data_ptr(), 7) == M.EINVAL          # wrong size
+    pageable = np.zeros(eng.expert_bytes, dtype=np.uint8)
+    assert lib.moe_spec_load_host_experts(eng.ctx, 0, 0, 1, pageable.ctypes.data, eng.expert_bytes) == M.EINVAL
+    assert b"pinned" in lib.moe_spec_last_error(eng.ctx)
+    eng.close()
+
+
+def test_stepping_a_layer_whose_tables_or_experts_are_missing():
+    wl = small_workload(n_layers=2, tokens=1)
+    cfg = M.Config(n_layers=2, hidden=wl.hidden, n_experts=wl.n_experts, top_k=wl.top_k, inter=wl.inter, max_batch=1,
+                   slots_per_layer=wl.slots, dtype=M.BF16, mode=M.MODE_ON_DEMAND, rms_eps=1e-6, copy_engine=M.COPY_KERNEL)
+    arena = torch.empty(M.moe_spec_arena_bytes(cfg), dtype=torch.uint8, device="cuda")
+    cs, ks = torch.cuda.Stream(), torch.cuda.Stream()
+    cfg.device_arena, cfg.device_arena_bytes = arena.data_ptr(), arena.numel()
+    cfg.compute_stream, cfg.copy_stream = cs.cuda_stream, ks.cuda_stream
+    ctx = M.moe_spec_create(cfg)
+    r = torch.randn(1, wl.hidden, device="cuda"); out = torch.empty_like(r)
+    torch.cuda.synchronize()
+    lib = M.lib()
+    M.moe_spec_begin_token(ctx)
+    assert lib.moe_spec_layer_step(ctx, 0, r.data_ptr(), 1, out.data_ptr(), None) == M.ESTATE    # no tables
+    res, ex, _ = build(wl)
+    from paper_2603_19289_amd.engine import _np_to_torch_storage
+    rw = _np_to_torch_storage(res["router_w"]).cuda(); dv = _np_to_torch_storage(res["dvecs"]).cuda()
+    gn = torch.from_numpy(res["rms_gain"]).cuda()
+    for l in range(2):
+        M.moe_spec_set_layer_resident(ctx, l, rw[l].data_ptr(), gn[l].data_ptr(), dv[l].data_ptr())
+    torch.cuda.synchronize()
+    assert lib.moe_spec_layer_step(ctx, 0, r.data_ptr(), 1, out.data_ptr(), None) == M.ESTATE    # no experts registered
+    assert b"never registered" in lib.moe_spec_last_error(ctx)
+    M.moe_spec_destroy(ctx)
+
+
+def _run_free(eng, wl, x0, eps):
+    """GPU runs free: its own outputs feed the synthetic residual driver."""
+    dev_x0, dev_eps = torch.from_numpy(x0).cuda(), torch.from_numpy(eps).cuda()
+    ids_log, outs = [], []
+    for t in range(x0.shape[0]):
+        eng.begin_token()
+        r = dev_x0[t].clone()
+        for l in range(wl.n_layers):
+            out, ids = eng.layer_step(l, r, want_ids=True)
+            ids_log.append({k: v for k, v in ids.items()})
+            outs.append(out)
+            if l + 1 < wl.n_layers:
+                with torch.cuda.stream(eng.compute):
+                    r = eng.advance(r, out, dev_eps[t, l], wl.res_a, wl.res_b)
+    torch.cuda.synchronize()
+    return ids_log, outs
+
+
+@pytest.mark.parametrize("mode", [M.MODE_ON_DEMAND, M.MODE_SPECULATIVE])
+def test_free_running_c1_matches_the_checker_with_margin_audit(mode):
+    # The GPU computes its own residual trajectory in float32.  Expert sets must still match the
+    # checker's unless the deciding logit margin is at rounding level; any mismatch with a
+    # comfortable margin is a bug.
+    wl = W.CONFIGS["c1_tiny"]
+    res, ex, model = build(wl, gains="ones")
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, mode, wl.slots)
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = _engine(wl, mode, res, ex)
+    ids_log, outs = _run_free(eng, wl, x0, eps)
+    mismatches = 0
+    i = 0
+    for t in range(wl.tokens):
+        for l in range(wl.n_layers):
+            want = trace[t][l][1]
+            got = ids_log[i]["true_ids"].cpu().numpy()
+            if not np.array_equal(np.sort(got), np.sort(want.true_ids)):
+                mismatches += 1
+                assert want.true_margin.min() < 1e-4, (t, l, got, want.true_ids, want.true_margin)
+            i += 1
+    st = eng.stats()
+    eng.close()
+    if mismatches == 0:
+        assert st["hits"] == orc.stats.hits and st["cache_misses"] == orc.stats.cache_misses
+        err = np.linalg.norm(outs[-1].cpu().numpy() - trace[-1][-1][1].out) / np.linalg.norm(trace[-1][-1][1].out)
+        assert err < 1e-4
+    print(f"[free-running] mode={mode} mismatching layer steps: {mismatches}", flush=True)
+
+
+def test_reset_makes_runs_repeatable_and_copy_engines_agree():
+    wl = small_workload(n_layers=4, hidden=264, n_experts=12, top_k=3, inter=200, tokens=6, slots=4, seed=21)
+    res, ex, _ = build(wl)
+    x0, eps = W.make_inputs(wl)
+    results = []
+    for engine_kind in (M.COPY_KERNEL, M.COPY_DMA):
+        eng = _engine(wl, M.MODE_SPECULATIVE, res, ex, copy_engine=engine_kind)
+        for rep in range(2):
+            eng.reset()
+            ids_log, outs = _run_free(eng, wl, x0, eps)
+            st = eng.stats()
+            results.append((torch.stack(outs).cpu().numpy(), torch.stack([d["exec_ids"] for d in ids_log]).cpu().numpy(),
+                            {k: st[k] for k in ("hits", "predictions", "cache_hits", "cache_misses", "h2d_bytes", "tokens")}))
+        eng.close()
+    for other in results[1:]:
+        np.testing.assert_array_equal(other[0], results[0][0])          # bit-identical outputs
+        np.testing.assert_array_equal(other[1], results[0][1])
+        assert other[2] == results[0][2]
+
+
+def test_smallest_pool_reuses_every_slot_without_corruption():
+    # S = k: every token overwrites every slot of every layer; with repeated inputs the outputs must
+    # repeat exactly, which fails if a copy ever lands in a slot that is still being read
+    wl = small_workload(n_layers=3, hidden=264, n_experts=12, top_k=3, inter=200, tokens=8, slots=3, seed=33)
+    res, ex, _ = build(wl)
+    x0, eps = W.make_inputs(wl)
+    x0[4:] = x0[:4]
+    eps[4:] = eps[:4]
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex)
+    _, outs = _run_free(eng, wl, x0, eps)
+    eng.close()
+    o = torch.stack(outs).cpu().numpy().reshape(8, wl.n_layers, -1)
+    np.testing.assert_array_equal(o[:4], o[4:])
