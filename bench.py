@@ -38,7 +38,9 @@ def parse():
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
     p.add_argument("--kernel-reps", type=int, default=480)
-    p.add_argument("--copy-engine", choices=["kernel", "dma"], default="kernel")
+    p.add_argument("--copy-engine", choices=["auto", "kernel", "dma", "dma2"], default="auto",
+                   help="auto: each mode gets the engine that is fastest for it (speculative: four DMA queues, "
+                        "on-demand: gather-copy kernel)")
     return p.parse_args()
 
 
@@ -77,12 +79,16 @@ def main():
     eps = torch.from_numpy(eps_np).to(dev)
     log(f"[bench] {wl.name}: pool {pool.numel() * pool.element_size() / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
 
-    copy_engine = M.COPY_KERNEL if args.copy_engine == "kernel" else M.COPY_DMA
+    codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
+    engine_names = {"speculative": "dma2" if args.copy_engine == "auto" else args.copy_engine,
+                    "on_demand": "kernel" if args.copy_engine == "auto" else args.copy_engine}
+    mode_codes = {"speculative": M.MODE_SPECULATIVE, "on_demand": M.MODE_ON_DEMAND}
 
-    def make(mode, profile):
-        return engine_for(wl, mode, res, pool, predict_in_on_demand=0, profile=profile, copy_engine=copy_engine)
+    def make(mode, profile, predict=0):
+        return engine_for(wl, mode_codes[mode], res, pool, predict_in_on_demand=predict, profile=profile,
+                          copy_engine=codes[engine_names[mode]])
 
-    engines = {"speculative": make(M.MODE_SPECULATIVE, 0), "on_demand": make(M.MODE_ON_DEMAND, 0)}
+    engines = {"speculative": make("speculative", 0), "on_demand": make("on_demand", 0)}
 
     def run_tokens(eng, t_first, n):
         out = torch.empty((B, H), dtype=torch.float32, device=dev)
@@ -129,13 +135,19 @@ def main():
 
     spec, ond = summary("speculative"), summary("on_demand")
 
-    # ---- breakdown with timing events (separate, instrumented contexts) and hit statistics
+    # ---- instrumented legs (separate contexts with timing events): compute / copy / stall breakdown,
+    #      hit statistics, and the duration of every gate/up kernel launch inside the token loop
     breakdown = {}
-    for mode, code in (("speculative", M.MODE_SPECULATIVE), ("on_demand", M.MODE_ON_DEMAND)):
+    gu_ms, gu_n = 0.0, 0
+    gemv_bytes = wl.top_k * 2 * wl.inter * H * wl.elem_bytes * 1.0
+    prof_eng = None
+    for mode in ("speculative", "on_demand"):
         engines[mode].close()
-        eng = engine_for(wl, code, res, pool, predict_in_on_demand=1, profile=1, copy_engine=copy_engine)
+        eng = make(mode, 1, predict=1)
         dt, d = timed(eng)
         busy = d["copy_ms"]
+        gu_ms += d["gateup_ms"]
+        gu_n += d["gateup_launches"]
         breakdown[mode] = {
             "wall_ms_per_token": dt / K * 1e3, "copy_ms_per_token": d["copy_ms"] / K,
             "compute_ms_per_token": d["compute_ms"] / K, "stall_ms_per_token": d["stall_ms"] / K,
@@ -144,22 +156,34 @@ def main():
             "link_frac_while_copying_nominal": d["h2d_bytes"] / (busy / 1e3) / 1e9 / LINK_PEAK_GBS if busy > 0 else None,
             "overlap_fraction": ((d["copy_ms"] + d["compute_ms"] - dt * 1e3) / min(d["copy_ms"], d["compute_ms"]))
             if min(d["copy_ms"], d["compute_ms"]) > 0 else None,
-            "hit_rate_recall_at_k": d["hits"] / max(1, d["predictions"])}
+            "hit_rate_recall_at_k": d["hits"] / max(1, d["predictions"]),
+            "gateup_us_per_launch_in_flow": d["gateup_ms"] / max(1, d["gateup_launches"]) * 1e3,
+            "gateup_gbs_in_flow": gemv_bytes / (d["gateup_ms"] / max(1, d["gateup_launches"]) / 1e3) / 1e9
+            if d["gateup_ms"] > 0 else None}
         if mode == "on_demand":
-            eng.close()
-        else:
             prof_eng = eng
+        else:
+            eng.close()
 
-    # ---- roofline of the dominant kernel (gate/up GEMV) and of the other two, on cold slots
+    # ---- roofline of the dominant kernel (gate/up GEMV).  achieved = algorithmic bytes per launch over the
+    #      mean launch duration inside the two instrumented token loops (event pairs on the compute stream);
+    #      the same kernels timed back to back on cold slots, without the token loop, are listed beside it
     kern = {}
-    for which, name in ((0, "expert_gateup_gemv"), (1, "expert_down_gemv"), (2, "router")):
+    for which, name in ((0, "expert_gateup_gemv"), (1, "expert_down_combine_gemv"), (2, "router")):
         ms, nbytes = prof_eng.time_kernel(which, args.kernel_reps)
-        kern[name] = {"ms_per_launch": ms, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
+        kern[name] = {"us_per_launch": ms * 1e3, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
     prof_eng.close()
     dom = kern["expert_gateup_gemv"]
-    roofline = {"bound": "hbm", "kernel": "gateup_b1_kernel (expert W_gate/W_up GEMV + SwiGLU, batch 1)", "achieved": dom["gbs"],
-                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS, "traffic": None,
-                "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"}}
+    roofline = {"bound": "hbm",
+                "kernel": "gateup_b1_kernel (expert W_gate/W_up GEMV + SwiGLU, batch 1)" if B == 1 else "gate/up expert kernel (batch 1 shape)",
+                "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS,
+                "traffic": None, "launches_timed": args.kernel_reps, "bytes_per_launch": dom["bytes_per_launch"],
+                "us_per_launch": dom["us_per_launch"],
+                "how": "two HIP events on the compute stream around back-to-back launches, each on the slots of the next layer",
+                "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"},
+                "in_token_loop_event_pairs": {m: {"us_per_launch": breakdown[m]["gateup_us_per_launch_in_flow"],
+                                                   "gbs": breakdown[m]["gateup_gbs_in_flow"]} for m in breakdown},
+                "in_token_loop_launches": gu_n}
 
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -197,7 +221,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + (" (REDUCED LAYERS, development run)" if reduced else ""),
                    "layers": L, "hidden": H, "experts": wl.n_experts, "top_k": wl.top_k, "inter": wl.inter,
-                   "batch": B, "slots_per_layer": wl.slots, "reps": args.reps, "copy_engine": args.copy_engine,
+                   "batch": B, "slots_per_layer": wl.slots, "reps": args.reps, "copy_engine": engine_names,
                    "expert_bytes": wl.expert_bytes, "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9},
         "speculative": spec, "on_demand": ond,
         "tpot_reduction_vs_on_demand": 1.0 - spec["tpot_ms"] / ond["tpot_ms"],

@@ -43,7 +43,7 @@ enum { MOE_SPEC_OK = 0, MOE_SPEC_EINVAL = -1, MOE_SPEC_ENOMEM = -2, MOE_SPEC_EST
        MOE_SPEC_EHIP = -4 };
 enum { MOE_SPEC_MODE_ON_DEMAND = 0, MOE_SPEC_MODE_SPECULATIVE = 1 };
 enum { MOE_SPEC_F32 = 0, MOE_SPEC_BF16 = 1 };   /* storage type of every weight table */
-enum { MOE_SPEC_COPY_DMA = 0, MOE_SPEC_COPY_KERNEL = 1 };
+enum { MOE_SPEC_COPY_DMA = 0, MOE_SPEC_COPY_KERNEL = 1, MOE_SPEC_COPY_DMA2 = 2 };
 
 /* limits checked by moe_spec_create */
 #define MOE_SPEC_MAX_EXPERTS 256
@@ -67,7 +67,11 @@ typedef struct {
   int32_t copy_engine;              /* how experts travel host -> device on the copy stream:
                                        0: one hipMemcpyAsync per expert (DMA engine);
                                        1: one gather-copy kernel per request that reads the pinned
-                                          pool directly (a few workgroups; keeps the link busier) */
+                                          pool directly (a few workgroups; keeps the link busier but
+                                          slows kernels that run beside it);
+                                       2: experts dealt round-robin to four DMA queues (copy_stream plus
+                                          three streams the library creates), so that one transfer's
+                                          set-up hides behind another's data */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
   size_t  device_arena_bytes;
   void   *compute_stream;           /* hipStream_t, borrowed; kernels run here */
@@ -85,6 +89,9 @@ typedef struct {
                                        time, time the compute stream spent waiting for a copy */
   double  wall_ms;                  /* host clock from the first begin_token after create/reset to
                                        the end of this call's synchronisation */
+  double  gateup_ms;                /* profile=1 only: summed duration of the gate/up expert kernel
+                                       launches, each bracketed by two events on the compute stream */
+  int64_t gateup_launches;
 } moe_spec_stats_t;
 
 /* Optional per-step outputs, each dev [B, k] or NULL.  ids are by descending logit. */

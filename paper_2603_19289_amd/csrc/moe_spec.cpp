@@ -38,7 +38,7 @@ struct Pool {                       // one layer's slot cache (least recently us
   long clock = 0;
 };
 
-struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall
+struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 gate/up kernel
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
@@ -60,7 +60,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->dtype != MOE_SPEC_F32 && c->dtype != MOE_SPEC_BF16) return "unknown dtype";
   if (c->mode != MOE_SPEC_MODE_ON_DEMAND && c->mode != MOE_SPEC_MODE_SPECULATIVE) return "unknown mode";
   if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
-  if (c->copy_engine != MOE_SPEC_COPY_DMA && c->copy_engine != MOE_SPEC_COPY_KERNEL) return "unknown copy_engine";
+  if (c->copy_engine < MOE_SPEC_COPY_DMA || c->copy_engine > MOE_SPEC_COPY_DMA2) return "unknown copy_engine";
   return nullptr;
 }
 
@@ -98,6 +98,10 @@ struct moe_spec_ctx {
   ArenaLayout lay{};
   char *arena = nullptr;
   hipStream_t compute = nullptr, copy = nullptr;
+  std::vector<hipStream_t> copy_aux;             // owned; further DMA queues of copy_engine 2
+  std::vector<hipEvent_t> aux_done;
+  int dma_queues = 4;
+  bool dma_split = false;                        // true: every expert cut in parts over all queues
 
   std::vector<const void *> router_w, gain, dvecs;
   std::vector<const char *> host_expert;        // [L*E]
@@ -168,7 +172,10 @@ struct moe_spec_ctx {
     for (auto &sp : spans) {
       float ms = 0.f;
       if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) {
-        if (sp.kind == 0) st.compute_ms += ms; else if (sp.kind == 1) st.copy_ms += ms; else st.stall_ms += ms;
+        if (sp.kind == 0) st.compute_ms += ms;
+        else if (sp.kind == 1) st.copy_ms += ms;
+        else if (sp.kind == 2) st.stall_ms += ms;
+        else { st.gateup_ms += ms; st.gateup_launches += 1; }
       }
       free_events.push_back(sp.a);
       free_events.push_back(sp.b);
@@ -230,6 +237,7 @@ struct moe_spec_ctx {
       if (copies == 0) {
         if (done_recorded[layer]) {
           hipError_t w = hipStreamWaitEvent(copy, done[layer], 0);
+          for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, done[layer], 0);
           if (w != hipSuccess) return hip_fail(w, "copy stream wait");
         }
         span = open_span(1, copy);
@@ -247,6 +255,19 @@ struct moe_spec_ctx {
           if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
           cl.n = 0;
         }
+      } else if (cfg.copy_engine == MOE_SPEC_COPY_DMA2) {
+        const size_t nq = 1 + copy_aux.size();
+        const size_t part = (expert_bytes / nq) & ~size_t(255);
+        hipError_t c = hipSuccess;
+        if (!dma_split) {                            // whole experts, round-robin over the queues
+          const size_t q = size_t(copies) % nq;
+          c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
+        } else
+        for (size_t q = 0; q < nq && c == hipSuccess; ++q) {
+          const size_t off = q * part, len = q + 1 == nq ? expert_bytes - off : part;
+          c = hipMemcpyAsync(dst + off, src + off, len, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
+        }
+        if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
       } else {
         hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, copy);
         if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
@@ -258,6 +279,13 @@ struct moe_spec_ctx {
     if (cl.n > 0) {
       hipError_t c = launch_gather_copy(cl, copy);
       if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
+    }
+    if (copies > 0) {                            // the request is complete when every queue is
+      for (size_t q = 0; q < copy_aux.size(); ++q) {
+        hipError_t r = hipEventRecord(aux_done[q], copy_aux[q]);
+        if (r == hipSuccess) r = hipStreamWaitEvent(copy, aux_done[q], 0);
+        if (r != hipSuccess) return hip_fail(r, "join copy queues");
+      }
     }
     if (copies > 0) {
       close_span(span, copy);
@@ -347,6 +375,18 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
     if ((e = hipEventCreateWithFlags(&c->ready[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     if ((e = hipEventCreateWithFlags(&c->done[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
+  if (cfg->copy_engine == MOE_SPEC_COPY_DMA2) {
+    if (const char *v = getenv("MOE_SPEC_DMA_QUEUES")) c->dma_queues = std::min(8, std::max(2, atoi(v)));
+    if (const char *v = getenv("MOE_SPEC_DMA_SPLIT")) c->dma_split = atoi(v) != 0;
+    for (int q = 1; q < c->dma_queues; ++q) {
+      hipStream_t sq = nullptr;
+      hipEvent_t ev = nullptr;
+      if ((e = hipStreamCreateWithFlags(&sq, hipStreamNonBlocking)) != hipSuccess) return bail(e, "auxiliary copy stream");
+      c->copy_aux.push_back(sq);
+      if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+      c->aux_done.push_back(ev);
+    }
+  }
   void *mb = nullptr;
   // fine-grained (coherent) pinned memory: device stores become visible to the spinning host
   if ((e = hipHostMalloc(&mb, 2 * sizeof(Mailbox), hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
@@ -371,7 +411,10 @@ void moe_spec_destroy(moe_spec_ctx *c) {
   if (c->compute || c->copy || c->mb_true) {
     (void)hipStreamSynchronize(c->compute);
     (void)hipStreamSynchronize(c->copy);
+    for (hipStream_t q : c->copy_aux) (void)hipStreamSynchronize(q);
   }
+  for (hipStream_t q : c->copy_aux) (void)hipStreamDestroy(q);
+  for (hipEvent_t ev : c->aux_done) (void)hipEventDestroy(ev);
   for (auto ev : c->ready) if (ev) (void)hipEventDestroy(ev);
   for (auto ev : c->done) if (ev) (void)hipEventDestroy(ev);
   for (auto &sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -573,6 +616,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     if (need_wait && (e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess)
       return c->hip_fail(e, "compute stream wait");
     if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
+    TimedSpan *sp_gu = c->open_span(3, c->compute);
     if (fast_b1) {
       // batch 1: the k executed experts are one wave; hand the kernels the slots in position order
       ActiveList by_pos{};
@@ -582,14 +626,17 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
         by_pos.slot[j] = int16_t(c->pools[layer].where[exec_ids_host[j]]);
       }
       if ((e = launch_gateup_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+      c->close_span(sp_gu, c->compute);
       if ((e = launch_down_combine_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
     } else if (use_mfma) {
       uint16_t *hq = c->at<uint16_t>(c->lay.h);
       if ((e = launch_gateup_mfma(xa, act, c->at<uint16_t>(c->lay.s_q), hq, c->compute)) != hipSuccess)
         return c->hip_fail(e, "gate/up MFMA kernel");
+      c->close_span(sp_gu, c->compute);
       if ((e = launch_down_mfma(xa, act, hq, c->compute)) != hipSuccess) return c->hip_fail(e, "down MFMA kernel");
     } else {
       if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+      c->close_span(sp_gu, c->compute);
       if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
     }
     if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");

@@ -13,7 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libmoe_spec.so")
 OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 MODE_ON_DEMAND, MODE_SPECULATIVE = 0, 1
 F32, BF16 = 0, 1
-COPY_DMA, COPY_KERNEL = 0, 1
+COPY_DMA, COPY_KERNEL, COPY_DMA2 = 0, 1, 2
 
 
 class Config(C.Structure):
@@ -31,7 +31,7 @@ class Stats(C.Structure):
                 ("hits", C.c_int64), ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
                 ("h2d_bytes", C.c_int64), ("hbm_bytes_algorithmic", C.c_int64),
                 ("copy_ms", C.c_double), ("compute_ms", C.c_double), ("stall_ms", C.c_double),
-                ("wall_ms", C.c_double)]
+                ("wall_ms", C.c_double), ("gateup_ms", C.c_double), ("gateup_launches", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -128,7 +128,7 @@ def test_reset_makes_runs_repeatable_and_copy_engines_agree():
     res, ex, _ = build(wl)
     x0, eps = W.make_inputs(wl)
     results = []
-    for engine_kind in (M.COPY_KERNEL, M.COPY_DMA):
+    for engine_kind in (M.COPY_KERNEL, M.COPY_DMA, M.COPY_DMA2):
         eng = _engine(wl, M.MODE_SPECULATIVE, res, ex, copy_engine=engine_kind)
         for rep in range(2):
             eng.reset()

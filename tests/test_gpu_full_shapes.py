@@ -40,7 +40,8 @@ def test_full_layer_shape_both_modes(name):
         run_teacher_forced(wl, MODES[mode], prebuilt=pre)
 
 
-def test_full_layer_shape_with_dma_copy_engine():
+@pytest.mark.parametrize("engine", ["COPY_DMA", "COPY_DMA2"])
+def test_full_layer_shape_with_dma_copy_engines(engine):
     from paper_2603_19289_amd import moe_spec as M
     wl = W.CONFIGS["c2_qwen3_30b_a3b"].with_(n_layers=2, tokens=2)
-    run_teacher_forced(wl, O.MODE_SPECULATIVE, prebuilt=prebuilt(wl), copy_engine=M.COPY_DMA)
+    run_teacher_forced(wl, O.MODE_SPECULATIVE, prebuilt=prebuilt(wl), copy_engine=getattr(M, engine))
