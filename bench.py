@@ -19,6 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per gate/up launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain
+# copy of known size (profiles/bench_c2_qwen3_pmc_hbm_traffic.md); only for the workload it was measured on
+PMC_TRAFFIC_BYTES = {"c2_qwen3_30b_a3b": 50504593}
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 
 
@@ -177,7 +180,7 @@ def main():
     roofline = {"bound": "hbm",
                 "kernel": "gateup_b1_kernel (expert W_gate/W_up GEMV + SwiGLU, batch 1)" if B == 1 else "gate/up expert kernel (batch 1 shape)",
                 "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS,
-                "traffic": None, "launches_timed": args.kernel_reps, "bytes_per_launch": dom["bytes_per_launch"],
+                "traffic": PMC_TRAFFIC_BYTES.get(wl.name) if not reduced else None, "launches_timed": args.kernel_reps, "bytes_per_launch": dom["bytes_per_launch"],
                 "us_per_launch": dom["us_per_launch"],
                 "how": "two HIP events on the compute stream around back-to-back launches, each on the slots of the next layer",
                 "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"},
