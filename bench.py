@@ -38,6 +38,8 @@ def parse():
     p.add_argument("--workload", default="c2_qwen3_30b_a3b")
     p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
     p.add_argument("--cpu-tokens", type=int, default=4, help="tokens the CPU checker is timed on (0 = skip)")
+    p.add_argument("--with-hint", action="store_true",
+                   help="also time the prefetch-as-hint policy (prefetch the prediction, execute the true experts, re-fetch misses)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
     p.add_argument("--kernel-reps", type=int, default=480)
@@ -85,13 +87,18 @@ def main():
     codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
     engine_names = {"speculative": "dma2" if args.copy_engine == "auto" else args.copy_engine,
                     "on_demand": "kernel" if args.copy_engine == "auto" else args.copy_engine}
-    mode_codes = {"speculative": M.MODE_SPECULATIVE, "on_demand": M.MODE_ON_DEMAND}
+    mode_codes = {"speculative": M.MODE_SPECULATIVE, "on_demand": M.MODE_ON_DEMAND,
+                  "prefetch_hint": M.MODE_PREFETCH_HINT}
+    if args.with_hint:
+        engine_names["prefetch_hint"] = "kernel" if args.copy_engine == "auto" else args.copy_engine
 
     def make(mode, profile, predict=0):
         return engine_for(wl, mode_codes[mode], res, pool, predict_in_on_demand=predict, profile=profile,
                           copy_engine=codes[engine_names[mode]])
 
     engines = {"speculative": make("speculative", 0), "on_demand": make("on_demand", 0)}
+    if args.with_hint:
+        engines["prefetch_hint"] = make("prefetch_hint", 0)
 
     def run_tokens(eng, t_first, n):
         out = torch.empty((B, H), dtype=torch.float32, device=dev)
@@ -137,6 +144,9 @@ def main():
                 "hbm_gb_algorithmic_per_token": d["hbm_bytes_algorithmic"] / K / 1e9}
 
     spec, ond = summary("speculative"), summary("on_demand")
+    hint = summary("prefetch_hint") if args.with_hint else None
+    if args.with_hint:
+        engines["prefetch_hint"].close()
 
     # ---- instrumented legs (separate contexts with timing events): compute / copy / stall breakdown,
     #      hit statistics, and the duration of every gate/up kernel launch inside the token loop
@@ -226,7 +236,7 @@ def main():
                    "layers": L, "hidden": H, "experts": wl.n_experts, "top_k": wl.top_k, "inter": wl.inter,
                    "batch": B, "slots_per_layer": wl.slots, "reps": args.reps, "copy_engine": engine_names,
                    "expert_bytes": wl.expert_bytes, "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9},
-        "speculative": spec, "on_demand": ond,
+        "speculative": spec, "on_demand": ond, "prefetch_hint": hint,
         "tpot_reduction_vs_on_demand": 1.0 - spec["tpot_ms"] / ond["tpot_ms"],
         "breakdown_instrumented": breakdown,
         "link": {"peak_nominal_gbs": LINK_PEAK_GBS, "achieved_gbs_speculative_wall": spec["h2d_gbs_wall"],

@@ -13,6 +13,9 @@
  * X_l (executed experts and their mixing weights) is the set predicted at layer l-1 in
  * speculative mode (layer 0 of a token is a cold start: true routing, blocking load), and the
  * true routing in on-demand mode, where the load of E_l blocks the expert computation.
+ * Prefetch-hint mode is the policy of earlier work the paper compares against (Sec. 2, Sec. 4): the
+ * predicted experts are prefetched as in speculative mode, but the true experts are executed, and
+ * those the prefetch missed are loaded on demand; its outputs equal on-demand mode's.
  * LN is RMSNorm with gain; TopK breaks ties towards the lower expert index; the mixing weights
  * are a softmax over the k selected logits.  Norms, router logits, top-k and gates are evaluated
  * in double precision; expert products accumulate in float.  With bf16 weights, s_l, q_l and the
@@ -41,7 +44,7 @@ typedef struct moe_spec_ctx moe_spec_ctx;   /* opaque, library-owned */
 
 enum { MOE_SPEC_OK = 0, MOE_SPEC_EINVAL = -1, MOE_SPEC_ENOMEM = -2, MOE_SPEC_ESTATE = -3,
        MOE_SPEC_EHIP = -4 };
-enum { MOE_SPEC_MODE_ON_DEMAND = 0, MOE_SPEC_MODE_SPECULATIVE = 1 };
+enum { MOE_SPEC_MODE_ON_DEMAND = 0, MOE_SPEC_MODE_SPECULATIVE = 1, MOE_SPEC_MODE_PREFETCH_HINT = 2 };
 enum { MOE_SPEC_F32 = 0, MOE_SPEC_BF16 = 1 };   /* storage type of every weight table */
 enum { MOE_SPEC_COPY_DMA = 0, MOE_SPEC_COPY_KERNEL = 1, MOE_SPEC_COPY_DMA2 = 2 };
 

@@ -28,6 +28,7 @@ import numpy as np
 
 MODE_ON_DEMAND = 0
 MODE_SPECULATIVE = 1
+MODE_PREFETCH_HINT = 2
 
 DTYPE_F32 = 0
 DTYPE_BF16 = 1
@@ -263,6 +264,9 @@ class MoEOracle:
     (the baseline of Sec. 5.1).  mode = MODE_SPECULATIVE: layer 0 is a cold start (route, blocking
     load); every later layer executes the experts *and mixing weights* predicted one layer
     earlier from the quasi-hidden state, and never re-fetches the true ones (Sec. 4).
+    mode = MODE_PREFETCH_HINT: the policy of prior work that the paper argues against (Sec. 2,
+    Sec. 4): the prediction is only a cache hint -- the predicted experts are prefetched, but the
+    true router-selected experts are executed and whatever the prefetch missed is loaded on demand.
 
     The true router runs at every layer in both modes: d_l is built from what "the router
     selects" at layer l (Sec. 3.1), and GetNextExperts is handed a fresh Gate_l(X).
@@ -276,7 +280,7 @@ class MoEOracle:
         self.mode = mode
         self.S = slots_per_layer
         self.q_from_normalized = q_from_normalized
-        self.predict = predict or mode == MODE_SPECULATIVE
+        self.predict = predict or mode in (MODE_SPECULATIVE, MODE_PREFETCH_HINT)
         self.bf16 = model.dtype == DTYPE_BF16
         self.pools = [LRUPool(slots_per_layer) for _ in range(model.n_layers)]
         self.stats = OracleStats()
@@ -354,7 +358,7 @@ class MoEOracle:
             if prefetched and w == 0:
                 continue          # requested during the previous layer step
             self._request(layer, wave)
-        if self.mode == MODE_SPECULATIVE and n_ids is not None:
+        if self.mode in (MODE_SPECULATIVE, MODE_PREFETCH_HINT) and n_ids is not None:
             nxt = chunks_of(sorted(set(n_ids.reshape(-1).tolist())), self.S)
             self._request(layer + 1, nxt[0])
 

@@ -58,7 +58,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->slots_per_layer < c->top_k) return "slots_per_layer must be at least top_k";
   if (c->slots_per_layer > 32767) return "slots_per_layer too large";
   if (c->dtype != MOE_SPEC_F32 && c->dtype != MOE_SPEC_BF16) return "unknown dtype";
-  if (c->mode != MOE_SPEC_MODE_ON_DEMAND && c->mode != MOE_SPEC_MODE_SPECULATIVE) return "unknown mode";
+  if (c->mode < MOE_SPEC_MODE_ON_DEMAND || c->mode > MOE_SPEC_MODE_PREFETCH_HINT) return "unknown mode";
   if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
   if (c->copy_engine < MOE_SPEC_COPY_DMA || c->copy_engine > MOE_SPEC_COPY_DMA2) return "unknown copy_engine";
   return nullptr;
@@ -107,7 +107,7 @@ struct moe_spec_ctx {
   std::vector<const char *> host_expert;        // [L*E]
   std::vector<Pool> pools;
   std::vector<hipEvent_t> ready, done;
-  std::vector<char> done_recorded;
+  std::vector<char> done_recorded, ready_recorded;
   Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
   Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
   uint32_t seq = 0;
@@ -240,6 +240,14 @@ struct moe_spec_ctx {
           for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, done[layer], 0);
           if (w != hipSuccess) return hip_fail(w, "copy stream wait");
         }
+        if (ready_recorded[layer]) {
+          // further queues: also behind the previous request on this pool (its slots may be reused
+          // by this one before any kernel ran, e.g. a true request right after a mispredicted prefetch)
+          for (hipStream_t q : copy_aux) {
+            hipError_t w = hipStreamWaitEvent(q, ready[layer], 0);
+            if (w != hipSuccess) return hip_fail(w, "copy queue wait");
+          }
+        }
         span = open_span(1, copy);
       }
       if (p.slot_expert[victim] >= 0) p.where[p.slot_expert[victim]] = -1;
@@ -291,6 +299,7 @@ struct moe_spec_ctx {
       close_span(span, copy);
       hipError_t r = hipEventRecord(ready[layer], copy);
       if (r != hipSuccess) return hip_fail(r, "record ready event");
+      ready_recorded[layer] = 1;
     }
     for (int e : experts) {
       act->expert[act->n] = int16_t(e);
@@ -362,6 +371,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   c->pools.resize(L);
   for (auto &p : c->pools) { p.slot_expert.assign(S, -1); p.slot_stamp.assign(S, -1); p.where.assign(E, -1); }
   c->done_recorded.assign(L, 0);
+  c->ready_recorded.assign(L, 0);
 
   auto bail = [&](hipError_t err, const char *what) {
     g_create_error = std::string(what) + ": " + hipGetErrorString(err);
@@ -494,8 +504,11 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   if (!c->router_w[layer] || (!last && !c->router_w[layer + 1]))
     return c->fail(MOE_SPEC_ESTATE, "resident tables of layer %d (or %d) were never set", layer, layer + 1);
   const bool spec_mode = cfg.mode == MOE_SPEC_MODE_SPECULATIVE;
-  const bool do_pred = !last && (spec_mode || cfg.predict_in_on_demand);
+  const bool hint_mode = cfg.mode == MOE_SPEC_MODE_PREFETCH_HINT;
+  const bool prefetching = spec_mode || hint_mode;
+  const bool do_pred = !last && (prefetching || cfg.predict_in_on_demand);
   const bool exec_pred = spec_mode && c->have_pending;
+  const bool hinted = hint_mode && c->have_pending;      // a prefetch for this layer may be in flight
   const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
   hipError_t e;
 
@@ -545,7 +558,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     pa.cmp_ids = nullptr;
     pa.user_ids = outs ? outs->next_ids : nullptr;
     pa.user_gates = outs ? outs->next_gates : nullptr;
-    pa.mailbox = spec_mode ? c->mb_next_dev : nullptr;
+    pa.mailbox = prefetching ? c->mb_next_dev : nullptr;
     ticket_next = ++c->seq;
     pa.seq = ticket_next;
     pa.spec = 1;
@@ -611,7 +624,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
       std::vector<int> req(exec_union.begin() + w0, exec_union.begin() + std::min(exec_union.size(), w0 + S));
       int rc = c->request(layer, req, &act, &copies);
       if (rc) return rc;
-      need_wait = copies > 0;
+      need_wait = copies > 0 || (hinted && wave == 0);
     }
     if (need_wait && (e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess)
       return c->hip_fail(e, "compute stream wait");
@@ -648,7 +661,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
 
   // --- prefetch the first wave of the predicted experts of layer l+1
   c->have_pending = do_pred;
-  if (do_pred && spec_mode) {
+  if (do_pred && prefetching) {
     int rc = c->wait_mailbox(c->mb_next, ticket_next);
     if (rc) return rc;
     c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
@@ -661,6 +674,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     if (copies == 0) {
       // nothing to copy: make the wait at the next step a no-op that is still well defined
       if ((e = hipEventRecord(c->ready[layer + 1], c->copy)) != hipSuccess) return c->hip_fail(e, "record ready event");
+      c->ready_recorded[layer + 1] = 1;
     }
   }
 

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoe_spec.so")
 
 OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
-MODE_ON_DEMAND, MODE_SPECULATIVE = 0, 1
+MODE_ON_DEMAND, MODE_SPECULATIVE, MODE_PREFETCH_HINT = 0, 1, 2
 F32, BF16 = 0, 1
 COPY_DMA, COPY_KERNEL, COPY_DMA2 = 0, 1, 2
 

@@ -12,7 +12,7 @@ from tests.helpers import build, make_advance, small_workload
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-5, "bf16": 2e-2}
-MODES = {"on_demand": O.MODE_ON_DEMAND, "speculative": O.MODE_SPECULATIVE}
+MODES = {"on_demand": O.MODE_ON_DEMAND, "speculative": O.MODE_SPECULATIVE, "prefetch_hint": O.MODE_PREFETCH_HINT}
 
 
 def rel_err(got, want):
@@ -118,6 +118,17 @@ def test_edge_shapes(mode):
 @pytest.mark.parametrize("mode", list(MODES))
 def test_caption_reading_of_the_quasi_hidden_state(mode):
     run_teacher_forced(small_workload(name="caption", n_layers=4, tokens=4), MODES[mode], q_from_normalized=1)
+
+
+@pytest.mark.parametrize("engine", ["COPY_DMA", "COPY_KERNEL", "COPY_DMA2"])
+def test_prefetch_hint_refetch_into_a_slot_the_prefetch_just_filled(engine):
+    # S = k: the true request of a layer reuses slots that the (mispredicted) prefetch for the same
+    # layer filled one step earlier, before any kernel read them; with several DMA queues the second
+    # copy must still land after the first
+    from paper_2603_19289_amd import moe_spec as M
+    wl = small_workload(name="hint_reuse", n_layers=4, hidden=264, n_experts=12, top_k=3, inter=200,
+                        dtype="bf16", batch=1, tokens=6, slots=3, seed=17)
+    run_teacher_forced(wl, O.MODE_PREFETCH_HINT, copy_engine=getattr(M, engine))
 
 
 def test_crafted_ties_pick_the_lower_index():

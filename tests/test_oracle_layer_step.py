@@ -191,3 +191,25 @@ def test_step_order_is_enforced_and_slots_must_cover_k():
     orc.begin_token()
     with pytest.raises(RuntimeError):
         orc.layer_step(1, np.zeros((1, wl.hidden)))
+
+
+def test_prefetch_hint_mode_executes_the_true_experts_and_counts_the_refetches():
+    # the prior-work policy: same outputs as on-demand, prefetch requests as in speculative mode,
+    # plus an on-demand request for the true set at every layer (hits where the prediction was right)
+    wl = small_workload(n_layers=4, dtype="bf16", batch=2, tokens=5, slots=4)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    hint, tr_h = _run(model, wl, O.MODE_PREFETCH_HINT, x0, adv)
+    ond, tr_o = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    requested = 0
+    for t in range(wl.tokens):
+        for l in range(wl.n_layers):
+            np.testing.assert_array_equal(tr_h[t][l][1].out, tr_o[t][l][1].out)
+            np.testing.assert_array_equal(tr_h[t][l][1].exec_ids, tr_h[t][l][1].true_ids)
+            requested += len(set(tr_h[t][l][1].true_ids.reshape(-1).tolist()))
+            if tr_h[t][l][1].next_ids is not None:
+                requested += min(wl.slots, len(set(tr_h[t][l][1].next_ids.reshape(-1).tolist())))
+    assert hint.stats.hits == ond.stats.hits and hint.stats.predictions == ond.stats.predictions
+    assert hint.stats.cache_hits + hint.stats.cache_misses == requested
+    assert hint.stats.cache_misses >= ond.stats.cache_misses - wl.slots * wl.n_layers   # mispredictions cost transfers
