@@ -76,13 +76,12 @@ def main():
 
     t_setup = time.time()
     res = W.make_resident(wl)
-    tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
-    pool = torch.empty((L, wl.n_experts, wl.expert_elems), dtype=tdtype, pin_memory=True)
+    pool = W.alloc_pinned_pool(wl)
     W.fill_experts_gpu(wl, pool)
     x0_np, eps_np = W.make_inputs(wl, tokens=T)
     x0 = torch.from_numpy(x0_np).to(dev)
     eps = torch.from_numpy(eps_np).to(dev)
-    log(f"[bench] {wl.name}: pool {pool.numel() * pool.element_size() / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
+    log(f"[bench] {wl.name}: pool {L * wl.n_experts * wl.expert_bytes / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
 
     codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
     engine_names = {"speculative": "dma2" if args.copy_engine == "auto" else args.copy_engine,
@@ -96,9 +95,7 @@ def main():
         return engine_for(wl, mode_codes[mode], res, pool, predict_in_on_demand=predict, profile=profile,
                           copy_engine=codes[engine_names[mode]])
 
-    engines = {"speculative": make("speculative", 0), "on_demand": make("on_demand", 0)}
-    if args.with_hint:
-        engines["prefetch_hint"] = make("prefetch_hint", 0)
+    modes = ["speculative", "on_demand"] + (["prefetch_hint"] if args.with_hint else [])
 
     def run_tokens(eng, t_first, n):
         out = torch.empty((B, H), dtype=torch.float32, device=dev)
@@ -113,6 +110,8 @@ def main():
                         r = eng.advance(r, out, eps[t, l], wl.res_a, wl.res_b, rbuf[l & 1])
 
     def timed(eng):
+        # one context alive at a time: every context owns streams, and idle ones would share the
+        # process's few hardware queues with the one being timed
         eng.reset()
         run_tokens(eng, 0, Wm)
         torch.cuda.synchronize()
@@ -125,10 +124,12 @@ def main():
         d = {k: after[k] - before[k] for k in after}
         return dt, d
 
-    results = {m: [] for m in engines}
+    results = {m: [] for m in modes}
     for rep in range(args.reps):
-        for mode, eng in engines.items():
+        for mode in modes:
+            eng = make(mode, 0)
             dt, d = timed(eng)
+            eng.close()
             results[mode].append((dt, d))
             log(f"[bench] rep {rep} {mode}: TPOT {dt / K * 1e3:.3f} ms, H2D {d['h2d_bytes'] / dt / 1e9:.2f} GB/s "
                 f"({d['cache_misses']} misses, {d['cache_hits']} hits)")
@@ -145,8 +146,6 @@ def main():
 
     spec, ond = summary("speculative"), summary("on_demand")
     hint = summary("prefetch_hint") if args.with_hint else None
-    if args.with_hint:
-        engines["prefetch_hint"].close()
 
     # ---- instrumented legs (separate contexts with timing events): compute / copy / stall breakdown,
     #      hit statistics, and the duration of every gate/up kernel launch inside the token loop
@@ -155,7 +154,6 @@ def main():
     gemv_bytes = wl.top_k * 2 * wl.inter * H * wl.elem_bytes * 1.0
     prof_eng = None
     for mode in ("speculative", "on_demand"):
-        engines[mode].close()
         eng = make(mode, 1, predict=1)
         dt, d = timed(eng)
         busy = d["copy_ms"]
@@ -210,7 +208,7 @@ def main():
     if args.cpu_tokens > 0:
         from oracle import moe_oracle as O
         n_tok = min(args.cpu_tokens, T)
-        pool_np = pool.view(torch.int16).numpy().view(np.uint16) if wl.dtype == "bf16" else pool.numpy()
+        pool_np = W.PoolView(pool)
         model = O.OracleModel(n_layers=L, hidden=H, n_experts=wl.n_experts, top_k=wl.top_k, inter=wl.inter,
                               dtype=O.DTYPE_BF16 if wl.dtype == "bf16" else O.DTYPE_F32, router_w=res["router_w"],
                               rms_gain=res["rms_gain"], dvecs=res["dvecs"], experts=pool_np)

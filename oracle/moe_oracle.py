@@ -238,6 +238,18 @@ class OracleStats:
 
 
 @dataclass
+class LayerDiagnostics:
+    """Statistics of the predictions made FOR one layer (at the layer before it), as in the
+    paper's per-layer figures: recall@k (Fig. 3), agreement per routing-weight rank (Fig. 4) and
+    cosine similarity between the predicting signal and the true router input (Fig. 2)."""
+    predictions: int = 0
+    hits: int = 0
+    rank_match: Optional[List[int]] = None
+    cos_sum: float = 0.0
+    cos_count: int = 0
+
+
+@dataclass
 class StepResult:
     out: np.ndarray            # [B, H] float64: O_l
     true_ids: np.ndarray       # [B, k] by descending logit
@@ -273,7 +285,7 @@ class MoEOracle:
     """
 
     def __init__(self, model: OracleModel, mode: int, slots_per_layer: int,
-                 q_from_normalized: bool = False, predict: bool = True):
+                 q_from_normalized: bool = False, predict: bool = True, predict_signal: int = 0):
         if slots_per_layer < model.top_k:
             raise ValueError("need at least k slots per layer")
         self.m = model
@@ -285,7 +297,12 @@ class MoEOracle:
         self.pools = [LRUPool(slots_per_layer) for _ in range(model.n_layers)]
         self.stats = OracleStats()
         self.pending: Optional[Tuple[np.ndarray, np.ndarray]] = None
+        self.pending_signal: Optional[np.ndarray] = None
         self.next_layer = 0
+        # 0: predict with the quasi-hidden state q_l; 1: with s_l, the baseline signal of Sec. 3.3
+        # (layer l+1's router applied to the normalised residual of layer l as it is)
+        self.predict_signal = predict_signal
+        self.diag = [LayerDiagnostics(rank_match=[0] * model.top_k) for _ in range(model.n_layers)]
 
     # -- cache bookkeeping ---------------------------------------------------------
     def _request(self, layer: int, experts: Sequence[int]):
@@ -297,6 +314,7 @@ class MoEOracle:
     def begin_token(self):
         """A new decode step: no prediction is carried into layer 0 (cold start)."""
         self.pending = None
+        self.pending_signal = None
         self.next_layer = 0
         self.stats.tokens += 1
 
@@ -326,9 +344,18 @@ class MoEOracle:
 
         # recall@k of the prediction made one layer earlier (Sec. 3.3)
         if self.pending is not None:
+            dg = self.diag[layer]
             for b in range(B):
-                self.stats.hits += len(set(self.pending[0][b].tolist()) & set(t_ids[b].tolist()))
+                h = len(set(self.pending[0][b].tolist()) & set(t_ids[b].tolist()))
+                self.stats.hits += h
                 self.stats.predictions += k
+                dg.hits += h
+                dg.predictions += k
+                for j in range(k):                      # same expert at the same routing-weight rank
+                    dg.rank_match[j] += int(self.pending[0][b, j] == t_ids[b, j])
+                sig = self.pending_signal[b]
+                dg.cos_sum += float(np.dot(sig, s[b]) / np.sqrt(np.dot(sig, sig) * np.dot(s[b], s[b])))
+                dg.cos_count += 1
 
         # which experts run, with which mixing weights (Algorithm 1, the if/else at the top)
         if self.mode == MODE_SPECULATIVE and self.pending is not None:
@@ -344,9 +371,12 @@ class MoEOracle:
             n_g = np.zeros((B, k))
             n_margin = np.zeros(B)
             for b in range(B):
-                d = layer_default_vector(m.dvecs[layer], t_ids[b], t_g[b])
-                q = quasi_hidden(r[b], s[b], d, m.rms_gain[layer + 1], m.rms_eps, self.bf16,
-                                 self.q_from_normalized)
+                if self.predict_signal == 1:
+                    q = s[b]
+                else:
+                    d = layer_default_vector(m.dvecs[layer], t_ids[b], t_g[b])
+                    q = quasi_hidden(r[b], s[b], d, m.rms_gain[layer + 1], m.rms_eps, self.bf16,
+                                     self.q_from_normalized)
                 q_all[b] = q
                 n_ids[b], n_g[b], n_margin[b] = self.route(layer + 1, q)
 
@@ -370,6 +400,7 @@ class MoEOracle:
                 out[b] += x_g[b, j] * expert_ffn(wg, wu, wd, s[b], self.bf16)
 
         self.pending = None if n_ids is None else (n_ids, n_g)
+        self.pending_signal = q_all
         self.next_layer = layer + 1
         self.stats.layer_steps += 1
         return StepResult(out, t_ids, t_g, np.array(x_ids), np.array(x_g), n_ids, n_g,

@@ -1,0 +1,91 @@
+// Device helpers shared by the kernel files: packed 16-byte weight chunks, bf16 rounding,
+// wavefront reductions with data-parallel primitives (DPP).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe_spec {
+
+constexpr int kWave = 64;
+
+// 16 bytes of stored weights: 8 bf16 (uint16_t bit patterns) or 4 floats.  Chunks stay packed in
+// registers while their loads are in flight and are unpacked to float where they are used.
+template <typename WT> struct Packed;
+template <> struct Packed<uint16_t> {
+  using Raw = uint4;
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void unpack(const uint4 &v, float (&f)[8]) {
+    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+  }
+  // x must already be a bf16 value held in a float
+  __device__ static __forceinline__ uint16_t pack_one(float x) { return uint16_t(__float_as_uint(x) >> 16); }
+};
+template <> struct Packed<float> {
+  using Raw = float4;
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void unpack(const float4 &v, float (&f)[4]) {
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+  __device__ static __forceinline__ float pack_one(float x) { return x; }
+};
+
+template <typename WT>
+__device__ __forceinline__ void load_chunk(const WT *p, float (&f)[Packed<WT>::N]) {
+  Packed<WT>::unpack(*reinterpret_cast<const typename Packed<WT>::Raw *>(p), f);
+}
+
+// float -> nearest bfloat16 (ties to even) -> float; finite inputs.
+__device__ __forceinline__ float round_to_bf16(float x) {
+  uint32_t u = __float_as_uint(x);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return __uint_as_float(u & 0xffff0000u);
+}
+
+// double -> nearest bfloat16 (8 significant bits, ties to even), straight from the double so
+// that nothing is rounded twice; normal-range inputs.
+__device__ __forceinline__ double round_to_bf16(double x) {
+  if (x == 0.0) return x;
+  int e;
+  const double m = frexp(x, &e);
+  return ldexp(rint(m * 256.0), e - 8);
+}
+
+// DPP controls used below: quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
+// row_half_mirror = 0x141, row_mirror = 0x140.  After the four steps every lane of a row of 16
+// holds the row's sum; one lane per row is then read through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double v) {
+  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+  return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ float readlane(float v, int src_lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src_lane));
+}
+
+__device__ __forceinline__ double readlane(double v, int src_lane) {
+  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
+  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
+  return __hiloint2double(hi, lo);
+}
+
+// Sum over the 64 lanes; every lane gets the same value.
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+  v += dpp_move<0xB1>(v);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0x141>(v);
+  v += dpp_move<0x140>(v);
+  return (readlane(v, 0) + readlane(v, 16)) + (readlane(v, 32) + readlane(v, 48));
+}
+
+}  // namespace moe_spec

@@ -7,6 +7,7 @@
 // [B,k] id table, stages their activation vectors in LDS, and each wavefront streams whole
 // weight rows with 16-byte loads per lane, reducing across the 64 lanes with shuffles.
 // Weights are read once per token tile; at batch 1 that is exactly once.
+#include "device_utils.h"
 #include "kernels.h"
 
 #include <cstdlib>
@@ -14,41 +15,8 @@
 namespace moe_spec {
 namespace {
 
-constexpr int kWave = 64;
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);
-  return v;
-}
-
-// float -> nearest bfloat16 (ties to even) -> float; finite inputs.
-__device__ __forceinline__ float round_to_bf16(float x) {
-  uint32_t u = __float_as_uint(x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return __uint_as_float(u & 0xffff0000u);
-}
-
-template <typename WT> struct Chunk;
-template <> struct Chunk<uint16_t> {
-  static constexpr int N = 8;
-  __device__ static void load(const uint16_t *p, float (&f)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4 *>(p);
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-};
-template <> struct Chunk<float> {
-  static constexpr int N = 4;
-  __device__ static void load(const float *p, float (&f)[4]) {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
-    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-  }
-};
 
 // Positions f = b*k + j of the id table that name expert e, in ascending order, by wavefront 0.
 __device__ __forceinline__ void gather_tokens(const int32_t *ids, int n_ids, int e, int *list,
@@ -76,7 +44,7 @@ __global__ __launch_bounds__(kBlock) void gateup_kernel(const ExpertArgs a, cons
   __shared__ int n_list;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int H = a.H, I = a.I;
-  constexpr int VN = Chunk<WT>::N;
+  constexpr int VN = Packed<WT>::N;
 
   const int e = act.expert[blockIdx.y];
   const WT *wg = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
@@ -104,8 +72,8 @@ __global__ __launch_bounds__(kBlock) void gateup_kernel(const ExpertArgs a, cons
 #pragma unroll 4
       for (int c = lane * VN; c < H; c += kWave * VN) {
         float fg[VN], fu[VN];
-        Chunk<WT>::load(pg + c, fg);
-        Chunk<WT>::load(pu + c, fu);
+        load_chunk<WT>(pg + c, fg);
+        load_chunk<WT>(pu + c, fu);
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
           if (t < nt) {
@@ -141,7 +109,7 @@ __global__ __launch_bounds__(kBlock) void down_kernel(const ExpertArgs a, const 
   __shared__ int n_list;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int H = a.H, I = a.I;
-  constexpr int VN = Chunk<WT>::N;
+  constexpr int VN = Packed<WT>::N;
 
   const int e = act.expert[blockIdx.y];
   const WT *wd = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes) +
@@ -168,7 +136,7 @@ __global__ __launch_bounds__(kBlock) void down_kernel(const ExpertArgs a, const 
 #pragma unroll 4
       for (int c = lane * VN; c < I; c += kWave * VN) {
         float fw[VN];
-        Chunk<WT>::load(pw + c, fw);
+        load_chunk<WT>(pw + c, fw);
 #pragma unroll
         for (int t = 0; t < TT; ++t) {
           if (t < nt) {
@@ -194,43 +162,6 @@ __global__ __launch_bounds__(kBlock) void down_kernel(const ExpertArgs a, const 
 // Batch-1 kernels: no token lists, no staging barrier in the gate/up kernel, combine fused into
 // the down kernel.  These are the kernels of the headline workload.
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
-}
-
-// Sum over the 64 lanes, result in every lane: two quad permutes and two mirrors inside each row of
-// 16 lanes (data-parallel primitives, no LDS traffic), then one lane of each row through scalars.
-__device__ __forceinline__ float wave_sum_dpp(float v) {
-  v += dpp_move<0xB1>(v);     // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);     // quad_perm [2,3,0,1]
-  v += dpp_move<0x141>(v);    // row_half_mirror
-  v += dpp_move<0x140>(v);    // row_mirror
-  const int i = __float_as_int(v);
-  return __int_as_float(__builtin_amdgcn_readlane(i, 0)) + __int_as_float(__builtin_amdgcn_readlane(i, 16)) +
-         __int_as_float(__builtin_amdgcn_readlane(i, 32)) + __int_as_float(__builtin_amdgcn_readlane(i, 48));
-}
-
-// Raw 16-byte weight chunks: kept packed in registers while in flight, unpacked at use.
-template <typename WT> struct Raw;
-template <> struct Raw<uint16_t> {
-  using T = uint4;
-  static constexpr int N = 8;
-  __device__ static void unpack(const uint4 &v, float (&f)[8]) {
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-  __device__ static uint16_t pack_one(float x) { return uint16_t(__float_as_uint(x) >> 16); }   // x is bf16-exact
-};
-template <> struct Raw<float> {
-  using T = float4;
-  static constexpr int N = 4;
-  __device__ static void unpack(const float4 &v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
-  __device__ static float pack_one(float x) { return x; }
-};
-
 // hq[pos, row] for the one token of the batch, stored in the weight dtype for the down kernel.
 // `act` is in execution-position order, so blockIdx.y is the position.  Each lane keeps its NCH
 // chunks of s_l in registers; a wavefront owns `rpw` consecutive rows and keeps the 2*NCH
@@ -238,7 +169,7 @@ template <> struct Raw<float> {
 template <typename WT, int NCH>
 __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, const ActiveList act,
                                                            const int rpw) {
-  using R = Raw<WT>;
+  using R = Packed<WT>;
   constexpr int VN = R::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int H = a.H, I = a.I;
@@ -258,11 +189,11 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
     live[ch] = col[ch] < H;
     if (!live[ch]) col[ch] = 0;                // dead lanes re-read column 0 and multiply by zero
   }
-  typename R::T rg[NCH], ru[NCH];
+  typename R::Raw rg[NCH], ru[NCH];
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch) {
-    rg[ch] = *reinterpret_cast<const typename R::T *>(wg + size_t(row0) * H + col[ch]);
-    ru[ch] = *reinterpret_cast<const typename R::T *>(wu + size_t(row0) * H + col[ch]);
+    rg[ch] = *reinterpret_cast<const typename R::Raw *>(wg + size_t(row0) * H + col[ch]);
+    ru[ch] = *reinterpret_cast<const typename R::Raw *>(wu + size_t(row0) * H + col[ch]);
   }
   float sv[NCH][VN];
 #pragma unroll
@@ -287,12 +218,12 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
     if (row + 1 < row_end) {
 #pragma unroll
       for (int ch = 0; ch < NCH; ++ch) {
-        rg[ch] = *reinterpret_cast<const typename R::T *>(wg + size_t(row + 1) * H + col[ch]);
-        ru[ch] = *reinterpret_cast<const typename R::T *>(wu + size_t(row + 1) * H + col[ch]);
+        rg[ch] = *reinterpret_cast<const typename R::Raw *>(wg + size_t(row + 1) * H + col[ch]);
+        ru[ch] = *reinterpret_cast<const typename R::Raw *>(wu + size_t(row + 1) * H + col[ch]);
       }
     }
-    const float g = wave_sum_dpp(ag);
-    const float u = wave_sum_dpp(au);
+    const float g = wave_sum(ag);
+    const float u = wave_sum(au);
     if (lane == 0) {
       float hv = g / (1.f + expf(-g)) * u;
       if (a.bf16) hv = round_to_bf16(hv);
@@ -310,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
 template <typename WT>
 __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArgs a, const ActiveList act,
                                                                  const float inv_chunks) {
-  using R = Raw<WT>;
+  using R = Packed<WT>;
   constexpr int VN = R::N;
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int H = a.H, I = a.I, k = a.k;
@@ -328,8 +259,8 @@ __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArg
     j += ((j + 1) * chunks <= t);
     const int c = (t - j * chunks) * VN;
     const char *base = a.pool + size_t(act.slot[j]) * a.slot_bytes + down_off;
-    const typename R::T w = *reinterpret_cast<const typename R::T *>(base + size_t(c) * sizeof(WT));
-    const typename R::T hh = *reinterpret_cast<const typename R::T *>(hq + size_t(j) * I + c);
+    const typename R::Raw w = *reinterpret_cast<const typename R::Raw *>(base + size_t(c) * sizeof(WT));
+    const typename R::Raw hh = *reinterpret_cast<const typename R::Raw *>(hq + size_t(j) * I + c);
     float fw[VN], fh[VN];
     R::unpack(w, fw);
     R::unpack(hh, fh);
@@ -338,7 +269,7 @@ __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArg
     for (int x = 0; x < VN; ++x) part += fw[x] * fh[x];
     acc += a.exec_gates[j] * part;
   }
-  const float v = wave_sum_dpp(acc);
+  const float v = wave_sum(acc);
   if (lane == 0) a.out[row] = v;
 }
 
@@ -538,7 +469,7 @@ void launch_gateup_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t 
 // Returns false when H needs more register chunks than the batch-1 kernel is built for.
 template <typename WT>
 bool launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
-  constexpr int VN = Raw<WT>::N;
+  constexpr int VN = Packed<WT>::N;
   const int need = (a.H + kWave * VN - 1) / (kWave * VN);
   if (need <= 1) launch_gateup_b1_n<WT, 1>(a, act, st);
   else if (need <= 2) launch_gateup_b1_n<WT, 2>(a, act, st);
@@ -553,7 +484,7 @@ bool launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st
 template <typename WT>
 void launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
   const dim3 grid((a.H + kWaves - 1) / kWaves), block(kBlock);
-  const float inv_chunks = 1.0f / float(a.I / Raw<WT>::N);
+  const float inv_chunks = 1.0f / float(a.I / Packed<WT>::N);
   hipLaunchKernelGGL((down_combine_b1_kernel<WT>), grid, block, 0, st, a, act, inv_chunks);
 }
 

@@ -10,75 +10,13 @@
 // previous prediction, and posts the ids to a pinned
 // host mailbox.  Everything that decides an expert index is double precision.
 // Layer order of the default-vector sum follows the id order (descending logit).
+#include "device_utils.h"
 #include "kernels.h"
 
 namespace moe_spec {
 namespace {
 
-constexpr int kWave = 64;
 constexpr int kMaxTokTile = 4;
-
-template <int CTRL>
-__device__ __forceinline__ double dpp_move_f64(double v) {
-  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
-  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
-  return __hiloint2double(hi, lo);
-}
-
-__device__ __forceinline__ double readlane_f64(double v, int src_lane) {
-  const int lo = __builtin_amdgcn_readlane(__double2loint(v), src_lane);
-  const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src_lane);
-  return __hiloint2double(hi, lo);
-}
-
-// Sum over the 64 lanes, the same value in every lane: quad permutes and mirrors inside each
-// row of 16 lanes, then one lane of each row through scalar registers.
-__device__ __forceinline__ double wave_sum(double v) {
-  v += dpp_move_f64<0xB1>(v);    // quad_perm [1,0,3,2]
-  v += dpp_move_f64<0x4E>(v);    // quad_perm [2,3,0,1]
-  v += dpp_move_f64<0x141>(v);   // row_half_mirror
-  v += dpp_move_f64<0x140>(v);   // row_mirror
-  return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
-}
-
-// Nearest bfloat16 (8 significant bits), ties to even, straight from the double.
-__device__ __forceinline__ double round_to_bf16(double x) {
-  if (x == 0.0) return x;
-  int e;
-  const double m = frexp(x, &e);
-  return ldexp(rint(m * 256.0), e - 8);
-}
-
-// 16 bytes of weights -> floats.  bf16: 8 values, float: 4 values.
-template <typename WT> struct Chunk;
-template <> struct Chunk<uint16_t> {
-  using Raw = uint4;
-  static constexpr int N = 8;
-  __device__ static void unpack(const uint4 &v, float (&f)[8]) {
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-  __device__ static void load(const uint16_t *p, float (&f)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4 *>(p);
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-  __device__ static float one(const uint16_t *p) { return __uint_as_float(uint32_t(*p) << 16); }
-};
-template <> struct Chunk<float> {
-  using Raw = float4;
-  static constexpr int N = 4;
-  __device__ static void unpack(const float4 &v, float (&f)[4]) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
-  __device__ static void load(const float *p, float (&f)[4]) {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
-    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
-  }
-  __device__ static float one(const float *p) { return *p; }
-};
 
 __device__ __forceinline__ double load_coherent(const double *p) {
   const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
@@ -99,7 +37,7 @@ __device__ __forceinline__ void rank_counts(const double (&key)[R], int lane, in
   for (int j = src_begin; j < src_end; ++j) {
 #pragma unroll
     for (int r2 = 0; r2 < R; ++r2) {
-      const double zj = readlane_f64(key[r2], j);
+      const double zj = readlane(key[r2], j);
       const int ij = r2 * kWave + j;
 #pragma unroll
       for (int r = 0; r < R; ++r)
@@ -192,8 +130,8 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   const WT *w = static_cast<const WT *>(a.w);
   const WT *dv = static_cast<const WT *>(a.dvec);
   const int H = a.H;
-  constexpr int VN = Chunk<WT>::N;
-  using Raw = typename Chunk<WT>::Raw;
+  constexpr int VN = Packed<WT>::N;
+  using Raw = typename Packed<WT>::Raw;
 
   constexpr int NREG = NCH > 0 ? NCH : 1;
   Raw wreg[NREG];
@@ -235,7 +173,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
               float dvf[VN];
-              Chunk<WT>::unpack(dr[q], dvf);
+              Packed<WT>::unpack(dr[q], dvf);
 #pragma unroll
               for (int x = 0; x < VN; ++x) d[x] += g[q] * double(dvf[x]);
             }
@@ -281,7 +219,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
           const int c = (ch * kWave + lane) * VN;
           if (c < H) {
             float wf[VN];
-            Chunk<WT>::unpack(wreg[ch], wf);
+            Packed<WT>::unpack(wreg[ch], wf);
 #pragma unroll
             for (int t = 0; t < kMaxTokTile; ++t) {
               if (t < nb) {
@@ -306,7 +244,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
             const int c = c0 + u * kWave * VN;
             if (c < H) {
               float wf[VN];
-              Chunk<WT>::unpack(wr4[u], wf);
+              Packed<WT>::unpack(wr4[u], wf);
 #pragma unroll
               for (int t = 0; t < kMaxTokTile; ++t) {
                 if (t < nb) {
@@ -380,7 +318,7 @@ hipError_t launch_route_n(const RouteArgs &args, size_t lds, hipStream_t st) {
 
 template <typename WT>
 hipError_t launch_route_t(const RouteArgs &args, size_t lds, hipStream_t st) {
-  const int need = (args.H + kWave * Chunk<WT>::N - 1) / (kWave * Chunk<WT>::N);
+  const int need = (args.H + kWave * Packed<WT>::N - 1) / (kWave * Packed<WT>::N);
   if (need <= 1) return launch_route_n<WT, 1>(args, lds, st);
   if (need <= 2) return launch_route_n<WT, 2>(args, lds, st);
   if (need <= 4) return launch_route_n<WT, 4>(args, lds, st);

@@ -58,8 +58,8 @@ class Engine:
             pool = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
             pool.copy_(t)
         else:
-            pool = experts
-            assert pool.is_pinned()
+            pool = experts                      # a pinned tensor [L,E,n] or a list of per-layer pinned tensors
+            assert all(pool[l].is_pinned() and pool[l].is_contiguous() for l in range(n_layers))
         self.pool = pool
         for l in range(n_layers):
             M.moe_spec_load_host_experts(self.ctx, l, 0, n_experts, pool[l].data_ptr(),

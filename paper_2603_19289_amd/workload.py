@@ -127,17 +127,62 @@ def make_experts_host(wl: Workload, out: Optional[np.ndarray] = None) -> np.ndar
     return out
 
 
+_hip_runtime = None
+
+
+def pinned_empty(n_elems: int, dtype: str):
+    """A page-locked host buffer of exactly n_elems weights as a 1-D torch tensor (bf16 or float32),
+    straight from hipHostMalloc.  torch's own pinned allocator rounds every request up to a power of
+    two, which the 38-90 GB pools cannot afford.  The buffer lives until the process ends."""
+    import ctypes
+    import torch
+    global _hip_runtime
+    if _hip_runtime is None:
+        _hip_runtime = ctypes.CDLL("libamdhip64.so")
+        _hip_runtime.hipHostMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t, ctypes.c_uint]
+    nbytes = n_elems * (2 if dtype == "bf16" else 4)
+    ptr = ctypes.c_void_p()
+    rc = _hip_runtime.hipHostMalloc(ctypes.byref(ptr), nbytes, 0)
+    if rc != 0 or not ptr.value:
+        raise MemoryError(f"hipHostMalloc of {nbytes} bytes failed with error {rc}")
+    raw = np.frombuffer((ctypes.c_uint8 * nbytes).from_address(ptr.value), dtype=np.uint8)
+    if dtype == "bf16":
+        return torch.from_numpy(raw.view(np.int16)).view(torch.bfloat16)
+    return torch.from_numpy(raw.view(np.float32))
+
+
+def alloc_pinned_pool(wl: Workload):
+    """Pinned host pool as a list of per-layer torch tensors [E, 3*H*I] in the storage dtype."""
+    return [pinned_empty(wl.n_experts * wl.expert_elems, wl.dtype).view(wl.n_experts, wl.expert_elems)
+            for _ in range(wl.n_layers)]
+
+
+class PoolView:
+    """Read-only numpy view of a per-layer pool, indexable as pool[layer, expert] (bf16 as uint16)."""
+
+    def __init__(self, layers):
+        import torch
+        self.layers = [t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+                       for t in layers]
+
+    def __getitem__(self, idx):
+        layer, e = idx
+        return self.layers[layer][e]
+
+
 def fill_experts_gpu(wl: Workload, pool, device="cuda") -> None:
-    """Fill a (pinned) torch tensor [L, E, 3*H*I] of the storage dtype with N(0, w_std^2) drawn by
-    torch's generator on the GPU, one layer at a time, and copy it down.  The CPU checker then reads
-    the very same bytes, so the device generator never has to be reproduced elsewhere."""
+    """Fill a pinned pool (a torch tensor [L, E, 3*H*I] or a list of per-layer tensors) with
+    N(0, w_std^2) drawn by torch's generator on the GPU, one layer at a time, and copy it down.
+    The CPU checker then reads the very same bytes, so the device generator never has to be
+    reproduced elsewhere."""
     import torch
     g = torch.Generator(device=device)
     for l in range(wl.n_layers):
         g.manual_seed((wl.seed << 20) + l)
-        buf = torch.empty(pool.shape[1:], dtype=torch.float32, device=device)
+        buf = torch.empty(tuple(pool[l].shape), dtype=torch.float32, device=device)
         buf.normal_(0.0, wl.w_std, generator=g)
-        pool[l].copy_(buf.to(pool.dtype))
+        pool[l].copy_(buf.to(pool[l].dtype))
+        del buf
     torch.cuda.synchronize()
 
 
