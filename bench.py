@@ -40,6 +40,9 @@ def parse():
     p.add_argument("--cpu-tokens", type=int, default=4, help="tokens the CPU checker is timed on (0 = skip)")
     p.add_argument("--with-hint", action="store_true",
                    help="also time the prefetch-as-hint policy (prefetch the prediction, execute the true experts, re-fetch misses)")
+    p.add_argument("--diagnostics", action="store_true",
+                   help="also collect per-layer recall@k, rank agreement and cosine similarity for the quasi-hidden "
+                        "state and for the baseline signal s_l (the statistics of the paper's per-layer figures)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
     p.add_argument("--kernel-reps", type=int, default=480)
@@ -84,7 +87,9 @@ def main():
     log(f"[bench] {wl.name}: pool {L * wl.n_experts * wl.expert_bytes / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
 
     codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
-    engine_names = {"speculative": "dma2" if args.copy_engine == "auto" else args.copy_engine,
+    # four DMA queues pay off from a few MB per expert on; below that their set-up latency dominates
+    spec_auto = "dma2" if wl.expert_bytes >= (4 << 20) else "kernel"
+    engine_names = {"speculative": spec_auto if args.copy_engine == "auto" else args.copy_engine,
                     "on_demand": "kernel" if args.copy_engine == "auto" else args.copy_engine}
     mode_codes = {"speculative": M.MODE_SPECULATIVE, "on_demand": M.MODE_ON_DEMAND,
                   "prefetch_hint": M.MODE_PREFETCH_HINT}
@@ -196,6 +201,21 @@ def main():
                                                    "gbs": breakdown[m]["gateup_gbs_in_flow"]} for m in breakdown},
                 "in_token_loop_launches": gu_n}
 
+    diagnostics = None
+    if args.diagnostics:
+        diagnostics = {}
+        for signal, name in ((0, "quasi_hidden_state"), (1, "baseline_s_l")):
+            eng = engine_for(wl, M.MODE_ON_DEMAND, res, pool, predict_in_on_demand=1, copy_engine=codes[engine_names["on_demand"]],
+                             predict_signal=signal, diagnostics=1)
+            run_tokens(eng, 0, min(T, 16))
+            per = [eng.layer_diagnostics(l) for l in range(L)]
+            eng.close()
+            diagnostics[name] = {
+                "tokens": min(T, 16), "execution": "true experts (on-demand), so both signals see the same trajectory",
+                "recall_at_k_per_layer": [round(d["hits"] / d["predictions"], 4) if d["predictions"] else None for d in per],
+                "cosine_to_next_router_input_per_layer": [round(d["cos_sum"] / d["cos_count"], 4) if d["cos_count"] else None for d in per],
+                "top_rank_agreement_per_layer": [round(d["rank_match"][0] / d["cos_count"], 4) if d["cos_count"] else None for d in per]}
+
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
@@ -239,7 +259,7 @@ def main():
         "breakdown_instrumented": breakdown,
         "link": {"peak_nominal_gbs": LINK_PEAK_GBS, "achieved_gbs_speculative_wall": spec["h2d_gbs_wall"],
                  "achieved_gbs_on_demand_wall": ond["h2d_gbs_wall"]},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "signal_diagnostics": diagnostics,
     }
     print(json.dumps(line), flush=True)
 

@@ -75,6 +75,11 @@ typedef struct {
                                        2: experts dealt round-robin to four DMA queues (copy_stream plus
                                           three streams the library creates), so that one transfer's
                                           set-up hides behind another's data */
+  int32_t predict_signal;           /* what layer l+1's router is run on to predict: 0 the quasi-hidden
+                                       state q_l (the method); 1 the normalised residual s_l as it is
+                                       (the baseline signal of Sec. 3.3) */
+  int32_t diagnostics;              /* 1: per-layer rank agreement and cosine similarity are collected
+                                       too (moe_spec_layer_diagnostics); recall per layer always is */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
   size_t  device_arena_bytes;
   void   *compute_stream;           /* hipStream_t, borrowed; kernels run here */
@@ -136,6 +141,20 @@ int moe_spec_begin_token(moe_spec_ctx *ctx);
  * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host. */
 int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
                         const moe_spec_step_outputs *outs);
+
+/* Statistics of the predictions made FOR one layer (at the layer before it): recall@k as in the
+ * paper's per-layer hit-rate figure, agreement per routing-weight rank as in its rank-alignment
+ * figure, and the cosine similarity between the predicting signal (q_{l-1} or s_{l-1}) and the true
+ * router input s_l as in its similarity figure.  The last two need diagnostics = 1. */
+typedef struct {
+  int64_t predictions, hits;
+  int64_t rank_match[MOE_SPEC_MAX_TOP_K];   /* tokens whose predicted expert at rank j is the true one */
+  double  cos_sum;                          /* sum over tokens; divide by cos_count */
+  int64_t cos_count;
+} moe_spec_layer_diag_t;
+
+/* Synchronises both streams, then copies layer `layer`'s statistics. */
+int moe_spec_layer_diagnostics(moe_spec_ctx *ctx, int layer, moe_spec_layer_diag_t *out);
 
 /* Synchronises both streams, then copies the counters. */
 int moe_spec_stats(moe_spec_ctx *ctx, moe_spec_stats_t *out);

@@ -19,10 +19,21 @@ struct Mailbox {
   uint32_t pad[15];
 };
 
+// Per-layer statistics of the predictions made for a layer, accumulated by the routing kernel
+// that computes the layer's true routing (paper: Sec. 3.3 recall@k; the per-rank agreement and the
+// cosine similarity of the figures in Sec. 3.3 and Sec. 4).
+struct LayerDiag {
+  unsigned long long hits, preds;
+  unsigned long long rank_match[kMaxTopK];   // same expert at the same routing-weight rank
+  double cos_sum;                            // sum over tokens of cos(predicting signal, s_l)
+  unsigned long long cos_count;
+};
+
 // Routing kernel: RMSNorm -> router GEMV -> top-k -> softmax over the selected logits.
 // spec = 0: input is r_l (true routing of layer l).
 // spec = 1: input is r_l (or s_l) + sum_j g_j d_{l,e_j}, normalised with layer l+1's gain and
 //           routed with layer l+1's router (the quasi-hidden state of Sec. 3.2).
+// spec = 2: input is s_l as it is, routed with layer l+1's router (the baseline signal of Sec. 3.3).
 struct RouteArgs {
   const float *r;             // [B,H]
   const float *s_in;          // [B,H] s_l, read when spec && from_normalized
@@ -39,7 +50,9 @@ struct RouteArgs {
   float *gates_out;           // [B,k]
   double *gates64_out;        // [B,k] or null
   const int32_t *cmp_ids;     // [B,k] prediction to score against this routing, or null
-  unsigned long long *hit_counters;   // [2] hits, predictions
+  LayerDiag *diag;            // statistics of the layer being routed (spec = 0)
+  const float *prev_signal;   // [B,H] the vector that predicted this layer, for the cosine; or null
+  int rank_stats;             // also count per-rank agreement
   int32_t *user_ids;          // optional copies for the caller
   float *user_gates;
   Mailbox *mailbox;           // pinned host, or null

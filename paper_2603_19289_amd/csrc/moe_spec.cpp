@@ -42,7 +42,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      hit_counters, h, y, bench_ids, s_q, total;
+      diag, h, y, bench_ids, s_q, sig, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -61,6 +61,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->mode < MOE_SPEC_MODE_ON_DEMAND || c->mode > MOE_SPEC_MODE_PREFETCH_HINT) return "unknown mode";
   if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
   if (c->copy_engine < MOE_SPEC_COPY_DMA || c->copy_engine > MOE_SPEC_COPY_DMA2) return "unknown copy_engine";
+  if (c->predict_signal != 0 && c->predict_signal != 1) return "unknown predict_signal";
   return nullptr;
 }
 
@@ -81,11 +82,12 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.true_gates = take(B * k * 4);
   a.true_gates64 = take(B * k * 8);
   for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
-  a.hit_counters = take(256);
+  a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.h = take(B * k * I * 4);
   a.y = take(B * k * H * 4);
   a.bench_ids = take(256);
   a.s_q = take(B * H * 2);
+  a.sig = take(B * H * 4);
   a.total = off;
   return a;
 }
@@ -410,7 +412,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   c->mb_next_dev = c->mb_true_dev + 1;
   // counters start at zero
   if ((e = hipMemsetAsync(c->arena + lay.counter, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counter");
-  if ((e = hipMemsetAsync(c->arena + lay.hit_counters, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counters");
+  if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return bail(e, "synchronize");
   *out = c;
   return MOE_SPEC_OK;
@@ -527,7 +529,9 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   ra.gates_out = c->at<float>(c->lay.true_gates);
   ra.gates64_out = c->at<double>(c->lay.true_gates64);
   ra.cmp_ids = c->have_pending ? c->at<int32_t>(c->lay.pend_ids[layer & 1]) : nullptr;
-  ra.hit_counters = c->at<unsigned long long>(c->lay.hit_counters);
+  ra.diag = c->at<LayerDiag>(c->lay.diag) + layer;
+  ra.rank_stats = cfg.diagnostics;
+  ra.prev_signal = cfg.diagnostics && c->have_pending ? c->at<float>(c->lay.sig) : nullptr;
   ra.user_ids = outs ? outs->true_ids : nullptr;
   ra.user_gates = outs ? outs->true_gates : nullptr;
   ra.mailbox = exec_pred ? nullptr : c->mb_true_dev;
@@ -550,8 +554,9 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     pa.dvec = c->dvecs[layer];
     pa.d_ids = c->at<int32_t>(c->lay.true_ids);
     pa.d_gates = c->at<double>(c->lay.true_gates64);
-    pa.vec_out = nullptr;
+    pa.vec_out = cfg.diagnostics ? c->at<float>(c->lay.sig) : nullptr;
     pa.vec_out_q = nullptr;
+    pa.prev_signal = nullptr;
     pa.ids_out = c->at<int32_t>(c->lay.pend_ids[(layer + 1) & 1]);
     pa.gates_out = c->at<float>(c->lay.pend_gates[(layer + 1) & 1]);
     pa.gates64_out = nullptr;
@@ -561,7 +566,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     pa.mailbox = prefetching ? c->mb_next_dev : nullptr;
     ticket_next = ++c->seq;
     pa.seq = ticket_next;
-    pa.spec = 1;
+    pa.spec = cfg.predict_signal == 1 ? 2 : 1;
     pa.from_normalized = cfg.q_from_normalized;
     if ((e = launch_route(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "prediction kernel");
     c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
@@ -693,14 +698,32 @@ int moe_spec_stats(moe_spec_ctx *c, moe_spec_stats_t *out) {
   if (e != hipSuccess) return c->hip_fail(e, "synchronize");
   int rc = c->resolve_spans();
   if (rc) return rc;
-  unsigned long long hc[2] = {0, 0};
-  if ((e = hipMemcpy(hc, c->arena + c->lay.hit_counters, sizeof hc, hipMemcpyDeviceToHost)) != hipSuccess)
+  std::vector<LayerDiag> dg(c->cfg.n_layers);
+  if ((e = hipMemcpy(dg.data(), c->arena + c->lay.diag, dg.size() * sizeof(LayerDiag), hipMemcpyDeviceToHost)) != hipSuccess)
     return c->hip_fail(e, "read hit counters");
-  c->st.hits = int64_t(hc[0]);
-  c->st.predictions = int64_t(hc[1]);
+  c->st.hits = c->st.predictions = 0;
+  for (const LayerDiag &d : dg) { c->st.hits += int64_t(d.hits); c->st.predictions += int64_t(d.preds); }
   if (c->clock_running)
     c->st.wall_ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - c->t0).count();
   *out = c->st;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_layer_diagnostics(moe_spec_ctx *c, int layer, moe_spec_layer_diag_t *out) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (!out) return c->fail(MOE_SPEC_EINVAL, "out is null");
+  if (layer < 0 || layer >= c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
+  hipError_t e = hipStreamSynchronize(c->compute);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->copy);
+  if (e != hipSuccess) return c->hip_fail(e, "synchronize");
+  LayerDiag d;
+  if ((e = hipMemcpy(&d, c->arena + c->lay.diag + size_t(layer) * sizeof(LayerDiag), sizeof d, hipMemcpyDeviceToHost)) != hipSuccess)
+    return c->hip_fail(e, "read layer statistics");
+  out->predictions = int64_t(d.preds);
+  out->hits = int64_t(d.hits);
+  for (int j = 0; j < MOE_SPEC_MAX_TOP_K; ++j) out->rank_match[j] = int64_t(d.rank_match[j]);
+  out->cos_sum = d.cos_sum;
+  out->cos_count = int64_t(d.cos_count);
   return MOE_SPEC_OK;
 }
 
@@ -717,7 +740,8 @@ int moe_spec_reset(moe_spec_ctx *c) {
     std::fill(p.where.begin(), p.where.end(), -1);
     p.clock = 0;
   }
-  if ((e = hipMemsetAsync(c->arena + c->lay.hit_counters, 0, 256, c->compute)) != hipSuccess) return c->hip_fail(e, "clear counters");
+  if ((e = hipMemsetAsync(c->arena + c->lay.diag, 0, size_t(c->cfg.n_layers) * sizeof(LayerDiag), c->compute)) != hipSuccess)
+    return c->hip_fail(e, "clear counters");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
   c->st = moe_spec_stats_t{};
   c->clock_running = false;
@@ -762,7 +786,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   ra.counter = c->at<unsigned int>(c->lay.counter);
   ra.ids_out = c->at<int32_t>(c->lay.true_ids);
   ra.gates_out = c->at<float>(c->lay.true_gates);
-  ra.hit_counters = c->at<unsigned long long>(c->lay.hit_counters);
+  ra.diag = c->at<LayerDiag>(c->lay.diag);
   ra.B = 1; ra.H = H; ra.E = E; ra.k = k; ra.eps = cfg.rms_eps; ra.bf16 = xa.bf16;
   const bool fast = b1_supported(H, cfg.dtype);
   hipError_t le = hipSuccess;

@@ -105,13 +105,14 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
         int hit = 0;
         for (int j = 0; j < a.k; ++j) hit |= (a.cmp_ids[size_t(b) * a.k + j] == id);
         if (hit) atomicAdd(&sh.hits, 1);
+        if (a.rank_stats && a.cmp_ids[o] == id) atomicAdd(&a.diag->rank_match[tid], 1ull);
       }
     }
     __syncthreads();
   }
   if (tid == 0 && a.cmp_ids) {
-    atomicAdd(&a.hit_counters[0], static_cast<unsigned long long>(sh.hits));
-    atomicAdd(&a.hit_counters[1], static_cast<unsigned long long>(a.k) * a.B);
+    atomicAdd(&a.diag->hits, static_cast<unsigned long long>(sh.hits));
+    atomicAdd(&a.diag->preds, static_cast<unsigned long long>(a.k) * a.B);
   }
 }
 
@@ -122,6 +123,7 @@ template <typename WT, int NCH>
 __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   extern __shared__ double vec[];            // [tok_tile][H]
   __shared__ double red[kRouteBlock / kWave];
+  __shared__ double red3[3][kRouteBlock / kWave];
   __shared__ int last_flag;
   __shared__ FinishShared fin;
 
@@ -148,6 +150,14 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
     for (int t = 0; t < nb; ++t) {
       const int b = b0 + t;
       double *v = vec + size_t(t) * H;
+      if (a.spec == 2) {                          // s_l as it is: no default vector, no second norm
+        for (int i = tid; i < H; i += kRouteBlock) {
+          const float x = a.s_in[size_t(b) * H + i];
+          v[i] = double(x);
+          if (blockIdx.x == 0 && a.vec_out) a.vec_out[size_t(b) * H + i] = x;
+        }
+        continue;
+      }
       double ss = 0.0;
       for (int c = tid * VN; c < H; c += kRouteBlock * VN) {     // VN consecutive elements per thread
         double u[VN];
@@ -205,6 +215,23 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
         if (blockIdx.x == 0 && a.vec_out) a.vec_out[size_t(b) * H + i] = static_cast<float>(n);
         if (blockIdx.x == 0 && a.vec_out_q)
           a.vec_out_q[size_t(b) * H + i] = uint16_t(__float_as_uint(static_cast<float>(n)) >> 16);
+      }
+      if (blockIdx.x == 0 && a.prev_signal) {     // cosine between the predicting signal and s_l
+        __syncthreads();
+        double dot = 0.0, pp = 0.0, qq = 0.0;
+        for (int i = tid; i < H; i += kRouteBlock) {
+          const double p = double(a.prev_signal[size_t(b) * H + i]), q = v[i];
+          dot += p * q; pp += p * p; qq += q * q;
+        }
+        dot = wave_sum(dot); pp = wave_sum(pp); qq = wave_sum(qq);
+        if (lane == 0) { red3[0][wave] = dot; red3[1][wave] = pp; red3[2][wave] = qq; }
+        __syncthreads();
+        if (tid == 0) {
+          double t[3];
+          for (int x = 0; x < 3; ++x) t[x] = (red3[x][0] + red3[x][1]) + (red3[x][2] + red3[x][3]);
+          atomicAdd(&a.diag->cos_sum, t[0] / sqrt(t[1] * t[2]));
+          atomicAdd(&a.diag->cos_count, 1ull);
+        }
       }
     }
     __syncthreads();

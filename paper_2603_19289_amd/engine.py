@@ -22,7 +22,7 @@ class Engine:
 
     def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
                  resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
-                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, device="cuda:0"):
+                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, device="cuda:0"):
         self.dev = torch.device(device)
         self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
         self.max_batch = max_batch
@@ -32,7 +32,8 @@ class Engine:
                        max_batch=max_batch, slots_per_layer=slots,
                        dtype=M.BF16 if dtype == "bf16" else M.F32, mode=mode, rms_eps=rms_eps,
                        q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
-                       profile=profile, copy_engine=copy_engine)
+                       profile=profile, copy_engine=copy_engine, predict_signal=predict_signal,
+                       diagnostics=diagnostics)
         need = M.moe_spec_arena_bytes(cfg)
         if need == 0:
             raise ValueError("invalid configuration")
@@ -101,6 +102,9 @@ class Engine:
 
     def stats(self) -> dict:
         return M.moe_spec_stats(self.ctx)
+
+    def layer_diagnostics(self, layer: int) -> dict:
+        return M.moe_spec_layer_diagnostics(self.ctx, layer)
 
     def reset(self):
         M.moe_spec_reset(self.ctx)

@@ -22,6 +22,7 @@ class Config(C.Structure):
                 ("slots_per_layer", C.c_int32), ("dtype", C.c_int32), ("mode", C.c_int32),
                 ("rms_eps", C.c_float), ("q_from_normalized", C.c_int32),
                 ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
+                ("predict_signal", C.c_int32), ("diagnostics", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
 
@@ -35,6 +36,11 @@ class Stats(C.Structure):
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class LayerDiag(C.Structure):
+    _fields_ = [("predictions", C.c_int64), ("hits", C.c_int64), ("rank_match", C.c_int64 * 16),
+                ("cos_sum", C.c_double), ("cos_count", C.c_int64)]
 
 
 class StepOutputs(C.Structure):
@@ -70,6 +76,7 @@ def lib():
         L.moe_spec_begin_token.argtypes = [vp]
         L.moe_spec_layer_step.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
         L.moe_spec_stats.argtypes = [vp, C.POINTER(Stats)]
+        L.moe_spec_layer_diagnostics.argtypes = [vp, i32, C.POINTER(LayerDiag)]
         L.moe_spec_reset.argtypes = [vp]
         L.moe_spec_destroy.argtypes = [vp]
         L.moe_spec_destroy.restype = None
@@ -121,6 +128,13 @@ def moe_spec_stats(ctx) -> dict:
     st = Stats()
     _check(lib().moe_spec_stats(ctx, C.byref(st)), ctx)
     return st.as_dict()
+
+
+def moe_spec_layer_diagnostics(ctx, layer: int) -> dict:
+    d = LayerDiag()
+    _check(lib().moe_spec_layer_diagnostics(ctx, layer, C.byref(d)), ctx)
+    return {"predictions": d.predictions, "hits": d.hits, "rank_match": list(d.rank_match),
+            "cos_sum": d.cos_sum, "cos_count": d.cos_count}
 
 
 def moe_spec_reset(ctx):

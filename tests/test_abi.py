@@ -49,7 +49,8 @@ def test_expert_and_arena_bytes():
 @pytest.mark.parametrize("bad", [dict(n_layers=0), dict(hidden=250), dict(hidden=16384), dict(inter=100),
                                  dict(n_experts=0), dict(n_experts=300), dict(top_k=0), dict(top_k=9),
                                  dict(top_k=17, n_experts=32), dict(max_batch=0), dict(max_batch=65),
-                                 dict(slots_per_layer=1), dict(dtype=7), dict(mode=5), dict(rms_eps=-1.0)])
+                                 dict(slots_per_layer=1), dict(dtype=7), dict(mode=5), dict(rms_eps=-1.0),
+                                 dict(predict_signal=2), dict(copy_engine=9)])
 def test_invalid_configurations_are_rejected(bad):
     cfg = good_config(**bad)
     assert M.moe_spec_arena_bytes(cfg) == 0

@@ -156,3 +156,33 @@ def test_smallest_pool_reuses_every_slot_without_corruption():
     eng.close()
     o = torch.stack(outs).cpu().numpy().reshape(8, wl.n_layers, -1)
     np.testing.assert_array_equal(o[:4], o[4:])
+
+
+@pytest.mark.parametrize("signal", [0, 1])
+@pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 3), ("bf16", 20)])
+def test_per_layer_diagnostics_match_the_checker(signal, dtype, B):
+    # recall, per-rank agreement and cosine similarity per layer, for the quasi-hidden state and for
+    # the baseline signal s_l; teacher-forced so that both sides see the same inputs
+    wl = small_workload(n_layers=5, hidden=264, n_experts=12, top_k=3, inter=200, dtype=dtype, batch=B,
+                        tokens=4, slots=12, seed=41)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots, predict_signal=signal)
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex, predict_signal=signal, diagnostics=1)
+    for t in range(wl.tokens):
+        eng.begin_token()
+        for l in range(wl.n_layers):
+            r = torch.from_numpy(trace[t][l][0].astype(np.float32)).cuda()
+            _, ids = eng.layer_step(l, r, want_ids=True)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), trace[t][l][1].exec_ids)
+    for l in range(wl.n_layers):
+        got, want = eng.layer_diagnostics(l), orc.diag[l]
+        assert got["predictions"] == want.predictions and got["hits"] == want.hits, l
+        assert got["rank_match"][:wl.top_k] == want.rank_match, l
+        assert got["cos_count"] == want.cos_count
+        assert abs(got["cos_sum"] - want.cos_sum) <= 1e-6 * max(1, want.cos_count), (l, got["cos_sum"], want.cos_sum)
+    st = eng.stats()
+    assert st["hits"] == orc.stats.hits and st["predictions"] == orc.stats.predictions
+    eng.close()

@@ -213,3 +213,49 @@ def test_prefetch_hint_mode_executes_the_true_experts_and_counts_the_refetches()
     assert hint.stats.hits == ond.stats.hits and hint.stats.predictions == ond.stats.predictions
     assert hint.stats.cache_hits + hint.stats.cache_misses == requested
     assert hint.stats.cache_misses >= ond.stats.cache_misses - wl.slots * wl.n_layers   # mispredictions cost transfers
+
+
+def test_per_layer_diagnostics_in_the_exact_prediction_construction():
+    # d = 0, no noise, W_down = 0: the predicting signal IS the next router input, so every rank
+    # agrees, cosine is 1 and recall is 1 at every layer; layer 0 is never predicted
+    wl = small_workload(n_layers=4, dtype="bf16", res_a=1.0, res_b=0.0, d_std=0.0, batch=2, tokens=3)
+    res, ex, _ = build(wl)
+    ex[:, :, 2 * wl.inter * wl.hidden:] = 0
+    model = oracle_model(wl, res, ex)
+    x0, eps = W.make_inputs(wl)
+    for signal in (0, 1):            # with unit gains and no drift the baseline signal s_l is exact too
+        orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots, predict_signal=signal)
+        O.run_tokens(orc, x0, make_advance(wl, eps))
+        assert orc.diag[0].predictions == 0 and orc.diag[0].cos_count == 0
+        for l in range(1, wl.n_layers):
+            d = orc.diag[l]
+            assert d.predictions == wl.top_k * wl.batch * wl.tokens == d.hits
+            assert d.rank_match == [wl.batch * wl.tokens] * wl.top_k
+            assert d.cos_count == wl.batch * wl.tokens and abs(d.cos_sum / d.cos_count - 1.0) < 1e-12
+        assert sum(d.hits for d in orc.diag) == orc.stats.hits
+
+
+def test_quasi_hidden_state_predicts_better_than_the_baseline_signal_when_defaults_carry_the_update():
+    # one-sample default vectors (d_{l,e} := the expert's real output): q_l is exact, while s_l
+    # ignores the block's contribution and the change of norm, so it must do worse
+    wl = small_workload(n_layers=4, dtype="f32", tokens=1, res_a=1.0, res_b=0.0, w_std=0.3)
+    res, ex, model = build(wl, gains="random")
+    x0, _ = W.make_inputs(wl)
+    adv = lambda t, l, r, out: r + out
+    dv = np.zeros((wl.n_layers, wl.n_experts, wl.hidden))
+    model.dvecs = dv
+    r = np.asarray(x0[0], dtype=np.float64)
+    for l in range(wl.n_layers):
+        s = O.rmsnorm(r[0], model.rms_gain[l], model.rms_eps)
+        for e in range(wl.n_experts):
+            dv[l, e] = O.expert_ffn(*model.expert_mats(l, e), s, False)
+        tr = O.run_tokens(O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots), x0, adv, n_layers=l + 1)
+        r = adv(0, l, tr[0][l][0], tr[0][l][1].out)
+    q_orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots, predict_signal=0)
+    s_orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots, predict_signal=1)
+    O.run_tokens(q_orc, x0, adv)
+    O.run_tokens(s_orc, x0, adv)
+    for l in range(1, wl.n_layers):
+        assert abs(q_orc.diag[l].cos_sum - 1.0) < 1e-12
+        assert s_orc.diag[l].cos_sum < 1.0 - 1e-4
+    assert q_orc.stats.hits == q_orc.stats.predictions
