@@ -80,6 +80,8 @@ typedef struct {
                                        (the baseline signal of Sec. 3.3) */
   int32_t diagnostics;              /* 1: per-layer rank agreement and cosine similarity are collected
                                        too (moe_spec_layer_diagnostics); recall per layer always is */
+  int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
+                                       feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
   size_t  device_arena_bytes;
   void   *compute_stream;           /* hipStream_t, borrowed; kernels run here */
@@ -125,6 +127,22 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out);
  * default_vecs dev [E,H] in the configured dtype, rms_gain dev [H] float.  Borrowed. */
 int moe_spec_set_layer_resident(moe_spec_ctx *ctx, int layer, const void *router_w,
                                 const void *rms_gain, const void *default_vecs);
+
+/* Weights of the neural expert estimator (paper: Sec. 6, Appendix A), forward pass only.  Every
+ * matrix is dev, row-major [out, in], in the configured dtype, 16-byte aligned: proj [dm, H] (the
+ * paper's A), layer_emb [L, dm], ffn_in [F, dm] (B), ffn_out [dm, F] (C), head [E, dm] (W_head);
+ * ln_gain, ln_bias dev [dm] float.  dm = est_latent, F = est_ffn of the configuration
+ * (MOE_SPEC_ESTATE if they are 0).  Borrowed.  The estimator maps the predicting signal of layer l
+ * to logits for layer l+1: latent = proj.q + emb_l; latent += ffn_out.silu(ffn_in.latent);
+ * logits = head.LayerNorm(latent); all in double precision. */
+int moe_spec_set_estimator(moe_spec_ctx *ctx, const void *proj, const void *layer_emb, const void *ffn_in,
+                           const void *ffn_out, const float *ln_gain, const float *ln_bias,
+                           const void *head, float ln_eps);
+
+/* use[l] != 0 (host, n_layers entries): the prediction made at layer l for layer l+1 takes the
+ * estimator's logits instead of layer l+1's router (all layers: the paper's Est-PF; the layers with
+ * low router hit rates only: Hybrid-PF).  Needs moe_spec_set_estimator first. */
+int moe_spec_set_estimator_layers(moe_spec_ctx *ctx, const uint8_t *use, int n_layers);
 
 /* Registers n_experts consecutive expert blocks of `layer`, starting at first_expert, that live at
  * pinned_host (host, page-locked: MOE_SPEC_EINVAL otherwise).  bytes must equal

@@ -141,6 +141,45 @@ def expert_ffn(w_gate, w_up, w_down, s, bf16):
 
 
 # --------------------------------------------------------------------------------------
+# Neural expert estimator (forward pass only)
+# --------------------------------------------------------------------------------------
+
+@dataclass
+class Estimator:
+    """Weights of the estimator of Sec. 6 / Appendix A, every matrix stored [out, in] row-major in the
+    model's weight dtype: proj [dm, H] (the paper's A, transposed storage), layer_emb [L, dm],
+    ffn_in [F, dm] (B), ffn_out [dm, F] (C), head [E, dm] (W_head); LayerNorm gain and bias [dm]
+    float.  dm = H/m, F = n*dm.  Only the forward pass exists here: training needs real activations."""
+    proj: np.ndarray
+    layer_emb: np.ndarray
+    ffn_in: np.ndarray
+    ffn_out: np.ndarray
+    ln_gain: np.ndarray
+    ln_bias: np.ndarray
+    head: np.ndarray
+    ln_eps: float = 1e-5
+
+
+def layernorm(x, gain, bias, eps):
+    """Standard LayerNorm: (x - mean) / sqrt(biased variance + eps) * gain + bias."""
+    x = np.asarray(x, dtype=np.float64)
+    mu = np.sum(x) / x.shape[-1]
+    var = np.sum((x - mu) * (x - mu)) / x.shape[-1]
+    return (x - mu) / np.sqrt(var + eps) * np.asarray(gain, dtype=np.float64) + np.asarray(bias, dtype=np.float64)
+
+
+def estimator_logits(est: Estimator, q, layer: int):
+    """Appendix A, in its order: project q_l to the latent size, add the embedding of layer l, feed
+    forward (linear, SiLU, linear) with a residual connection over it, LayerNorm, linear head to E
+    logits for layer l+1.  No rounding inside (the paper fixes none); weights as stored."""
+    u = decode_weights(est.proj) @ np.asarray(q, dtype=np.float64) + decode_weights(est.layer_emb[layer])
+    t = silu(decode_weights(est.ffn_in) @ u)
+    v = u + decode_weights(est.ffn_out) @ t
+    w = layernorm(v, est.ln_gain, est.ln_bias, est.ln_eps)
+    return decode_weights(est.head) @ w
+
+
+# --------------------------------------------------------------------------------------
 # Device expert cache, simulated (integers only)
 # --------------------------------------------------------------------------------------
 
@@ -285,7 +324,8 @@ class MoEOracle:
     """
 
     def __init__(self, model: OracleModel, mode: int, slots_per_layer: int,
-                 q_from_normalized: bool = False, predict: bool = True, predict_signal: int = 0):
+                 q_from_normalized: bool = False, predict: bool = True, predict_signal: int = 0,
+                 estimator: Optional[Estimator] = None, estimator_layers: Optional[Sequence[int]] = None):
         if slots_per_layer < model.top_k:
             raise ValueError("need at least k slots per layer")
         self.m = model
@@ -302,6 +342,10 @@ class MoEOracle:
         # 0: predict with the quasi-hidden state q_l; 1: with s_l, the baseline signal of Sec. 3.3
         # (layer l+1's router applied to the normalised residual of layer l as it is)
         self.predict_signal = predict_signal
+        # Est-PF / Hybrid-PF of Sec. 6: at the layers named here the prediction for layer l+1 comes from
+        # the estimator's logits instead of layer l+1's router (all layers: Est-PF; some: Hybrid-PF)
+        self.estimator = estimator
+        self.estimator_layers = set(estimator_layers or []) if estimator is not None else set()
         self.diag = [LayerDiagnostics(rank_match=[0] * model.top_k) for _ in range(model.n_layers)]
 
     # -- cache bookkeeping ---------------------------------------------------------
@@ -378,7 +422,12 @@ class MoEOracle:
                     q = quasi_hidden(r[b], s[b], d, m.rms_gain[layer + 1], m.rms_eps, self.bf16,
                                      self.q_from_normalized)
                 q_all[b] = q
-                n_ids[b], n_g[b], n_margin[b] = self.route(layer + 1, q)
+                if layer in self.estimator_layers:
+                    z = estimator_logits(self.estimator, q, layer)
+                    n_ids[b] = topk_desc(z, k)
+                    n_g[b], n_margin[b] = gates_of(z, n_ids[b]), _margin(z, k)
+                else:
+                    n_ids[b], n_g[b], n_margin[b] = self.route(layer + 1, q)
 
         # cache traffic: what has to be resident, in waves of at most S experts
         exec_union = sorted(set(x_ids.reshape(-1).tolist()))

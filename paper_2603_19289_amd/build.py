@@ -4,7 +4,8 @@ import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libmoe_spec.so")
-SOURCES = ["csrc/moe_spec.cpp", "csrc/route_kernels.hip", "csrc/expert_kernels.hip", "csrc/synth.hip"]
+SOURCES = ["csrc/moe_spec.cpp", "csrc/route_kernels.hip", "csrc/expert_kernels.hip",
+           "csrc/estimator_kernels.hip", "csrc/synth.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function"]

@@ -34,11 +34,15 @@ struct LayerDiag {
 // spec = 1: input is r_l (or s_l) + sum_j g_j d_{l,e_j}, normalised with layer l+1's gain and
 //           routed with layer l+1's router (the quasi-hidden state of Sec. 3.2).
 // spec = 2: input is s_l as it is, routed with layer l+1's router (the baseline signal of Sec. 3.3).
+// spec = 3: input is x_f64 [B,H] (the estimator's latent vector), LayerNorm with gain and bias,
+//           then the estimator's head as the "router" (Appendix A); H is the latent size.
 struct RouteArgs {
   const float *r;             // [B,H]
   const float *s_in;          // [B,H] s_l, read when spec && from_normalized
   const void *w;              // [E,H] router weights of the layer being routed
   const float *gain;          // [H] gain of that layer's norm
+  const float *bias;          // [H] LayerNorm bias (spec = 3)
+  const double *x_f64;        // [B,H] input of spec = 3
   const void *dvec;           // spec: [E,H] default vectors of layer l
   const int32_t *d_ids;       // spec: [B,k] true ids of layer l
   const double *d_gates;      // spec: [B,k] true gates of layer l
@@ -91,6 +95,18 @@ struct CopyList {
   int32_t total_wgs, unroll;       // launch shape: workgroups over all blocks, loads in flight per lane
 };
 hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st);
+
+// Double-precision GEMV used by the estimator: y = act(W x + add_w) + add_f64.
+struct GemvArgs {
+  const void *w;              // [rows, cols] in the weight dtype
+  const float *x_f32;         // [B, cols], or null when x_f64 is given
+  const double *x_f64;        // [B, cols]
+  const void *add_w;          // [rows] in the weight dtype, added before the activation, or null
+  const double *add_f64;      // [B, rows] added after the activation, or null
+  double *y;                  // [B, rows]
+  int B, rows, cols, silu;
+};
+hipError_t launch_gemv64(const GemvArgs &a, int dtype, hipStream_t st);
 
 hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);

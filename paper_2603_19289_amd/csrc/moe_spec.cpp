@@ -42,7 +42,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, total;
+      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -62,6 +62,9 @@ const char *validate(const moe_spec_config *c) {
   if (!(c->rms_eps >= 0.f)) return "rms_eps must be >= 0";
   if (c->copy_engine < MOE_SPEC_COPY_DMA || c->copy_engine > MOE_SPEC_COPY_DMA2) return "unknown copy_engine";
   if (c->predict_signal != 0 && c->predict_signal != 1) return "unknown predict_signal";
+  if (c->est_latent < 0 || c->est_ffn < 0 || (c->est_latent == 0) != (c->est_ffn == 0)) return "estimator sizes must both be set or both be 0";
+  if (c->est_latent % 8 || c->est_ffn % 8) return "estimator sizes must be multiples of 8";
+  if (c->est_latent > MOE_SPEC_MAX_HIDDEN || c->est_ffn > 8 * MOE_SPEC_MAX_HIDDEN) return "estimator sizes too large";
   return nullptr;
 }
 
@@ -88,6 +91,9 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.bench_ids = take(256);
   a.s_q = take(B * H * 2);
   a.sig = take(B * H * 4);
+  a.est_u = take(B * size_t(c->est_latent) * 8);
+  a.est_t = take(B * size_t(c->est_ffn) * 8);
+  a.est_v = take(B * size_t(c->est_latent) * 8);
   a.total = off;
   return a;
 }
@@ -106,6 +112,8 @@ struct moe_spec_ctx {
   bool dma_split = false;                        // true: every expert cut in parts over all queues
 
   std::vector<const void *> router_w, gain, dvecs;
+  struct { const void *proj, *layer_emb, *ffn_in, *ffn_out, *head; const float *ln_gain, *ln_bias; float ln_eps; bool set; } est{};
+  std::vector<char> est_use;                    // [L] predict with the estimator at this layer
   std::vector<const char *> host_expert;        // [L*E]
   std::vector<Pool> pools;
   std::vector<hipEvent_t> ready, done;
@@ -479,6 +487,32 @@ int moe_spec_load_host_experts(moe_spec_ctx *c, int layer, int first_expert, int
   return MOE_SPEC_OK;
 }
 
+int moe_spec_set_estimator(moe_spec_ctx *c, const void *proj, const void *layer_emb, const void *ffn_in,
+                           const void *ffn_out, const float *ln_gain, const float *ln_bias, const void *head,
+                           float ln_eps) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (c->cfg.est_latent == 0) return c->fail(MOE_SPEC_ESTATE, "the configuration names no estimator sizes");
+  if (!proj || !layer_emb || !ffn_in || !ffn_out || !ln_gain || !ln_bias || !head)
+    return c->fail(MOE_SPEC_EINVAL, "null estimator pointer");
+  const uintptr_t all = reinterpret_cast<uintptr_t>(proj) | reinterpret_cast<uintptr_t>(layer_emb) |
+                        reinterpret_cast<uintptr_t>(ffn_in) | reinterpret_cast<uintptr_t>(ffn_out) |
+                        reinterpret_cast<uintptr_t>(head);
+  if (all & 15) return c->fail(MOE_SPEC_EINVAL, "estimator matrices must be 16-byte aligned");
+  if (!(ln_eps >= 0.f)) return c->fail(MOE_SPEC_EINVAL, "ln_eps must be >= 0");
+  c->est.proj = proj; c->est.layer_emb = layer_emb; c->est.ffn_in = ffn_in; c->est.ffn_out = ffn_out;
+  c->est.head = head; c->est.ln_gain = ln_gain; c->est.ln_bias = ln_bias; c->est.ln_eps = ln_eps;
+  c->est.set = true;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_set_estimator_layers(moe_spec_ctx *c, const uint8_t *use, int n_layers) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (!use || n_layers != c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "need one flag per layer");
+  if (!c->est.set) return c->fail(MOE_SPEC_ESTATE, "set the estimator's weights first");
+  c->est_use.assign(use, use + n_layers);
+  return MOE_SPEC_OK;
+}
+
 int moe_spec_begin_token(moe_spec_ctx *c) {
   if (!c) return MOE_SPEC_EINVAL;
   if (c->cfg.profile) { int rc = c->resolve_spans(); if (rc) return rc; }
@@ -568,8 +602,50 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
     pa.seq = ticket_next;
     pa.spec = cfg.predict_signal == 1 ? 2 : 1;
     pa.from_normalized = cfg.q_from_normalized;
-    if ((e = launch_route(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "prediction kernel");
-    c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+    const bool use_est = c->est.set && !c->est_use.empty() && c->est_use[layer];
+    if (use_est) {
+      // The routing launch only produces the predicting signal; the estimator's four steps turn it
+      // into logits, and its last step (the routing kernel in LayerNorm mode) selects and hands over.
+      RouteArgs sa = pa;
+      sa.vec_out = c->at<float>(c->lay.sig);
+      sa.user_ids = nullptr;
+      sa.user_gates = nullptr;
+      sa.mailbox = nullptr;
+      if ((e = launch_route(sa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "signal kernel");
+      const int dm = cfg.est_latent, F = cfg.est_ffn;
+      GemvArgs g{};
+      g.B = batch;
+      g.w = c->est.proj; g.x_f32 = c->at<float>(c->lay.sig); g.rows = dm; g.cols = H;
+      g.add_w = static_cast<const char *>(c->est.layer_emb) + size_t(layer) * dm * wbytes;
+      g.y = c->at<double>(c->lay.est_u);
+      if ((e = launch_gemv64(g, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "estimator projection");
+      g = GemvArgs{};
+      g.B = batch;
+      g.w = c->est.ffn_in; g.x_f64 = c->at<double>(c->lay.est_u); g.rows = F; g.cols = dm; g.silu = 1;
+      g.y = c->at<double>(c->lay.est_t);
+      if ((e = launch_gemv64(g, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "estimator feed-forward");
+      g = GemvArgs{};
+      g.B = batch;
+      g.w = c->est.ffn_out; g.x_f64 = c->at<double>(c->lay.est_t); g.rows = dm; g.cols = F;
+      g.add_f64 = c->at<double>(c->lay.est_u);
+      g.y = c->at<double>(c->lay.est_v);
+      if ((e = launch_gemv64(g, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "estimator feed-forward");
+      RouteArgs ha = pa;
+      ha.spec = 3;
+      ha.x_f64 = c->at<double>(c->lay.est_v);
+      ha.w = c->est.head;
+      ha.gain = c->est.ln_gain;
+      ha.bias = c->est.ln_bias;
+      ha.eps = c->est.ln_eps;
+      ha.H = dm;
+      ha.vec_out = nullptr;
+      if ((e = launch_route(ha, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "estimator head");
+      c->st.hbm_bytes_algorithmic += (int64_t(dm) * H + 2 * int64_t(F) * dm + int64_t(E) * dm + dm) * wbytes +
+                                     int64_t(batch) * k * H * wbytes;
+    } else {
+      if ((e = launch_route(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "prediction kernel");
+      c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+    }
   }
   c->close_span(sp_route, c->compute);
 

@@ -150,6 +150,29 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
     for (int t = 0; t < nb; ++t) {
       const int b = b0 + t;
       double *v = vec + size_t(t) * H;
+      if (a.spec == 3) {                          // LayerNorm of the estimator's latent vector
+        double sum = 0.0;
+        for (int i = tid; i < H; i += kRouteBlock) {
+          const double x = a.x_f64[size_t(b) * H + i];
+          v[i] = x;
+          sum += x;
+        }
+        sum = wave_sum(sum);
+        __syncthreads();
+        if (lane == 0) red[wave] = sum;
+        __syncthreads();
+        const double mean = ((red[0] + red[1]) + (red[2] + red[3])) / double(H);
+        double sq = 0.0;
+        for (int i = tid; i < H; i += kRouteBlock) { const double d = v[i] - mean; sq += d * d; }
+        sq = wave_sum(sq);
+        __syncthreads();
+        if (lane == 0) red[wave] = sq;
+        __syncthreads();
+        const double root = sqrt(((red[0] + red[1]) + (red[2] + red[3])) / double(H) + double(a.eps));
+        for (int i = tid; i < H; i += kRouteBlock)
+          v[i] = (v[i] - mean) / root * double(a.gain[i]) + double(a.bias[i]);
+        continue;
+      }
       if (a.spec == 2) {                          // s_l as it is: no default vector, no second norm
         for (int i = tid; i < H; i += kRouteBlock) {
           const float x = a.s_in[size_t(b) * H + i];

@@ -22,7 +22,8 @@ class Engine:
 
     def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
                  resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
-                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, device="cuda:0"):
+                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, estimator=None,
+                 estimator_layers=None, device="cuda:0"):
         self.dev = torch.device(device)
         self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
         self.max_batch = max_batch
@@ -33,7 +34,9 @@ class Engine:
                        dtype=M.BF16 if dtype == "bf16" else M.F32, mode=mode, rms_eps=rms_eps,
                        q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
                        profile=profile, copy_engine=copy_engine, predict_signal=predict_signal,
-                       diagnostics=diagnostics)
+                       diagnostics=diagnostics,
+                       est_latent=0 if estimator is None else estimator["proj"].shape[0],
+                       est_ffn=0 if estimator is None else estimator["ffn_in"].shape[0])
         need = M.moe_spec_arena_bytes(cfg)
         if need == 0:
             raise ValueError("invalid configuration")
@@ -53,6 +56,16 @@ class Engine:
         for l in range(n_layers):
             M.moe_spec_set_layer_resident(self.ctx, l, self.router_w[l].data_ptr(), self.rms_gain[l].data_ptr(),
                                           self.dvecs[l].data_ptr())
+        if estimator is not None:
+            self.est = {k: (torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)) if k.startswith("ln_")
+                            else _np_to_torch_storage(v)).to(self.dev) for k, v in estimator.items()}
+            M.moe_spec_set_estimator(self.ctx, *(self.est[k].data_ptr() for k in
+                                                 ("proj", "layer_emb", "ffn_in", "ffn_out", "ln_gain", "ln_bias", "head")),
+                                     1e-5)
+            use = [0] * n_layers
+            for l in (estimator_layers if estimator_layers is not None else range(n_layers)):
+                use[l] = 1
+            M.moe_spec_set_estimator_layers(self.ctx, use)
         # host pool: [L, E, 3*H*I] in storage dtype, pinned
         if isinstance(experts, np.ndarray):
             t = _np_to_torch_storage(experts)

@@ -23,6 +23,7 @@ class Config(C.Structure):
                 ("rms_eps", C.c_float), ("q_from_normalized", C.c_int32),
                 ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
                 ("predict_signal", C.c_int32), ("diagnostics", C.c_int32),
+                ("est_latent", C.c_int32), ("est_ffn", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
 
@@ -73,6 +74,8 @@ def lib():
         L.moe_spec_create.argtypes = [C.POINTER(Config), C.POINTER(vp)]
         L.moe_spec_set_layer_resident.argtypes = [vp, i32, vp, vp, vp]
         L.moe_spec_load_host_experts.argtypes = [vp, i32, i32, i32, vp, sz]
+        L.moe_spec_set_estimator.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, C.c_float]
+        L.moe_spec_set_estimator_layers.argtypes = [vp, C.POINTER(C.c_uint8), i32]
         L.moe_spec_begin_token.argtypes = [vp]
         L.moe_spec_layer_step.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
         L.moe_spec_stats.argtypes = [vp, C.POINTER(Stats)]
@@ -113,6 +116,15 @@ def moe_spec_set_layer_resident(ctx, layer, router_w_ptr, rms_gain_ptr, default_
 
 def moe_spec_load_host_experts(ctx, layer, first_expert, n_experts, pinned_host_ptr, nbytes):
     _check(lib().moe_spec_load_host_experts(ctx, layer, first_expert, n_experts, pinned_host_ptr, nbytes), ctx)
+
+
+def moe_spec_set_estimator(ctx, proj, layer_emb, ffn_in, ffn_out, ln_gain, ln_bias, head, ln_eps):
+    _check(lib().moe_spec_set_estimator(ctx, proj, layer_emb, ffn_in, ffn_out, ln_gain, ln_bias, head, ln_eps), ctx)
+
+
+def moe_spec_set_estimator_layers(ctx, use):
+    arr = (C.c_uint8 * len(use))(*[1 if u else 0 for u in use])
+    _check(lib().moe_spec_set_estimator_layers(ctx, arr, len(use)), ctx)
 
 
 def moe_spec_begin_token(ctx):

@@ -17,7 +17,7 @@ from typing import Dict, Optional
 import numpy as np
 
 _FAMILY = {"router": 1, "dvec": 2, "expert": 3, "x0": 4, "eps": 5, "center": 6, "eta0": 7,
-           "eps_cluster": 8, "gain": 9}
+           "eps_cluster": 8, "gain": 9, "estimator": 10}
 
 
 @dataclass(frozen=True)
@@ -111,6 +111,21 @@ def make_resident(wl: Workload, gains: str = "ones") -> Dict[str, np.ndarray]:
                          for l in range(L)]).astype(np.float32)
     return {"router_w": to_storage(router, wl.dtype), "rms_gain": gain,
             "dvecs": to_storage(dv, wl.dtype)}
+
+
+def make_estimator(wl: Workload, m: int = 4, n: int = 2) -> Dict[str, np.ndarray]:
+    """Random weights in the shapes of the paper's estimator (Appendix A; trained weights do not exist
+    here): latent size dm = H/m, feed-forward size F = n*dm.  Every matrix is stored [out, in]."""
+    H, E, L = wl.hidden, wl.n_experts, wl.n_layers
+    dm, F = H // m, n * (H // m)
+    g = lambda i, shape, std: _rng(wl.seed, "estimator", i).standard_normal(shape, dtype=np.float32) * std
+    return {"proj": to_storage(g(0, (dm, H), 1.0 / np.sqrt(H)), wl.dtype),
+            "layer_emb": to_storage(g(1, (L, dm), 0.5), wl.dtype),
+            "ffn_in": to_storage(g(2, (F, dm), 1.0 / np.sqrt(dm)), wl.dtype),
+            "ffn_out": to_storage(g(3, (dm, F), 1.0 / np.sqrt(F)), wl.dtype),
+            "ln_gain": (1.0 + 0.1 * g(4, (dm,), 1.0)).astype(np.float32),
+            "ln_bias": (0.1 * g(5, (dm,), 1.0)).astype(np.float32),
+            "head": to_storage(g(6, (E, dm), 1.0 / np.sqrt(dm)), wl.dtype)}
 
 
 def make_experts_host(wl: Workload, out: Optional[np.ndarray] = None) -> np.ndarray:

@@ -19,7 +19,8 @@ def rel_err(got, want):
     return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
 
 
-def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", prebuilt=None, **engine_kw):
+def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", prebuilt=None, oracle_kw=None,
+                       **engine_kw):
     """The checker runs free; the GPU step is fed the checker's r_l at every layer.
     prebuilt = (resident tables, checker model, pinned torch pool) for pools drawn on the GPU."""
     from paper_2603_19289_amd.engine import engine_for
@@ -30,7 +31,7 @@ def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", 
     else:
         res, model, ex = prebuilt
     x0, eps = W.make_inputs(wl)
-    orc = O.MoEOracle(model, mode, wl.slots, q_from_normalized=bool(q_from_normalized))
+    orc = O.MoEOracle(model, mode, wl.slots, q_from_normalized=bool(q_from_normalized), **(oracle_kw or {}))
     trace = O.run_tokens(orc, x0, make_advance(wl, eps))
     eng = engine_for(wl, mode, res, ex, q_from_normalized=q_from_normalized, **engine_kw)
     worst = 0.0
@@ -129,6 +130,19 @@ def test_prefetch_hint_refetch_into_a_slot_the_prefetch_just_filled(engine):
     wl = small_workload(name="hint_reuse", n_layers=4, hidden=264, n_experts=12, top_k=3, inter=200,
                         dtype="bf16", batch=1, tokens=6, slots=3, seed=17)
     run_teacher_forced(wl, O.MODE_PREFETCH_HINT, copy_engine=getattr(M, engine))
+
+
+@pytest.mark.parametrize("layers", [None, [1, 3]], ids=["est_pf", "hybrid_pf"])
+@pytest.mark.parametrize("dtype,B", [("bf16", 1), ("f32", 1), ("bf16", 5)])
+def test_estimator_predictions(layers, dtype, B):
+    # the estimator's forward pass (random weights in the paper's shapes) replaces the router-based
+    # prediction at all layers (Est-PF) or at some (Hybrid-PF); the speculated experts are executed
+    wl = small_workload(name="estimator", n_layers=5, hidden=264, n_experts=12, top_k=3, inter=200,
+                        dtype=dtype, batch=B, tokens=4, slots=6, seed=51)
+    est = W.make_estimator(wl, m=3, n=2)            # latent 88, feed-forward 176
+    use = list(range(wl.n_layers)) if layers is None else layers
+    run_teacher_forced(wl, O.MODE_SPECULATIVE, oracle_kw=dict(estimator=O.Estimator(**est), estimator_layers=use),
+                       estimator=est, estimator_layers=use)
 
 
 def test_crafted_ties_pick_the_lower_index():

@@ -259,3 +259,20 @@ def test_quasi_hidden_state_predicts_better_than_the_baseline_signal_when_defaul
         assert abs(q_orc.diag[l].cos_sum - 1.0) < 1e-12
         assert s_orc.diag[l].cos_sum < 1.0 - 1e-4
     assert q_orc.stats.hits == q_orc.stats.predictions
+
+
+def test_estimator_replaces_the_router_only_at_the_named_layers():
+    wl = small_workload(n_layers=4, dtype="bf16", tokens=3)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    e = W.make_estimator(wl, m=4, n=2)
+    est = O.Estimator(**e)
+    plain, tr_p = _run(model, wl, O.MODE_ON_DEMAND, x0, adv)
+    hybrid, tr_h = _run(model, wl, O.MODE_ON_DEMAND, x0, adv, estimator=est, estimator_layers=[1])
+    for t in range(wl.tokens):
+        np.testing.assert_array_equal(tr_h[t][0][1].next_ids, tr_p[t][0][1].next_ids)      # layer 0: router
+        np.testing.assert_array_equal(tr_h[t][2][1].next_ids, tr_p[t][2][1].next_ids)      # layer 2: router
+        z = O.estimator_logits(est, tr_h[t][1][1].q[0], 1)
+        assert tr_h[t][1][1].next_ids[0].tolist() == O.topk_desc(z, wl.top_k).tolist()     # layer 1: estimator
+    assert any(not np.array_equal(tr_h[t][1][1].next_ids, tr_p[t][1][1].next_ids) for t in range(wl.tokens))

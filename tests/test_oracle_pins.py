@@ -224,3 +224,48 @@ def test_lru_pool_as_large_as_the_expert_set_misses_each_expert_once():
 def test_chunks_of():
     assert O.chunks_of([1, 2, 3, 4, 5], 2) == [[1, 2], [3, 4], [5]]
     assert O.chunks_of([1, 2], 4) == [[1, 2]]
+
+
+# ------------------------------------------------------------------ estimator forward
+def test_layernorm_hand_value_and_library():
+    np.testing.assert_allclose(O.layernorm([1.0, 3.0], [2.0, 1.0], [0.5, -1.0], 0.0), [-1.5, 0.0], rtol=1e-15)
+    rng = np.random.default_rng(6)
+    x, g, b = rng.standard_normal(70), rng.standard_normal(70), rng.standard_normal(70)
+    want = torch.nn.functional.layer_norm(torch.from_numpy(x), (70,), torch.from_numpy(g), torch.from_numpy(b), 1e-5).numpy()
+    np.testing.assert_allclose(O.layernorm(x, g, b, 1e-5), want, rtol=1e-12, atol=1e-14)
+
+
+def _random_estimator(rng, H, dm, F, E, L):
+    f = lambda *s: rng.standard_normal(s).astype(np.float32)
+    return O.Estimator(proj=f(dm, H), layer_emb=f(L, dm), ffn_in=f(F, dm), ffn_out=f(dm, F),
+                       ln_gain=f(dm), ln_bias=f(dm), head=f(E, dm))
+
+
+def test_estimator_forward_matches_library_modules():
+    rng = np.random.default_rng(7)
+    H, dm, F, E, L = 24, 6, 18, 10, 3
+    est = _random_estimator(rng, H, dm, F, E, L)
+    q = rng.standard_normal(H)
+    Fn = torch.nn.functional
+    t = lambda a: torch.from_numpy(np.asarray(a, dtype=np.float64))
+    for layer in range(L):
+        u = Fn.linear(t(q), t(est.proj)) + t(est.layer_emb[layer])
+        v = u + Fn.linear(Fn.silu(Fn.linear(u, t(est.ffn_in))), t(est.ffn_out))
+        w = Fn.layer_norm(v, (dm,), t(est.ln_gain), t(est.ln_bias), est.ln_eps)
+        np.testing.assert_allclose(O.estimator_logits(est, q, layer), Fn.linear(w, t(est.head)).numpy(), rtol=1e-11, atol=1e-13)
+    # the layer embedding matters, and so does the residual connection
+    assert np.abs(O.estimator_logits(est, q, 0) - O.estimator_logits(est, q, 1)).max() > 1e-3
+
+
+def test_estimator_special_cases():
+    rng = np.random.default_rng(8)
+    H, dm, F, E, L = 8, 4, 8, 4, 2
+    est = _random_estimator(rng, H, dm, F, E, L)
+    est.ffn_out[:] = 0                                     # dead feed-forward branch: only the residual path is left
+    est.head = np.eye(E, dm, dtype=np.float32)             # logits = LayerNorm output
+    est.ln_gain[:] = 1
+    est.ln_bias[:] = 0
+    q = rng.standard_normal(H)
+    u = est.proj.astype(np.float64) @ q + est.layer_emb[1]
+    want = (u - u.mean()) / np.sqrt(u.var() + est.ln_eps)
+    np.testing.assert_allclose(O.estimator_logits(est, q, 1), want, rtol=1e-12)
