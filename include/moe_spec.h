@@ -80,6 +80,11 @@ typedef struct {
                                        (the baseline signal of Sec. 3.3) */
   int32_t diagnostics;              /* 1: per-layer rank agreement and cosine similarity are collected
                                        too (moe_spec_layer_diagnostics); recall per layer always is */
+  int32_t accumulate_defaults;      /* 1: keep, per layer and expert, the running sum and count of the
+                                       un-gated outputs of every executed expert (the offline statistic
+                                       behind the default vectors, Sec. 3.1); costs L*E*H doubles of arena
+                                       and disables the fused batch-1 down+combine kernel */
+  int32_t reserved0;
   int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
                                        feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
@@ -173,6 +178,12 @@ typedef struct {
 
 /* Synchronises both streams, then copies layer `layer`'s statistics. */
 int moe_spec_layer_diagnostics(moe_spec_ctx *ctx, int layer, moe_spec_layer_diag_t *out);
+
+/* accumulate_defaults = 1 only (MOE_SPEC_ESTATE otherwise): writes the mean un-gated output of each
+ * expert of `layer` over the steps that executed it to mean_dev (dev [E,H] float, zero rows for experts
+ * never executed) and the number of executions to counts_host (host [E], may be NULL).  These means
+ * are the per-expert default vectors d_{l,e} of Sec. 3.1.  Synchronises the compute stream. */
+int moe_spec_read_default_vectors(moe_spec_ctx *ctx, int layer, float *mean_dev, int64_t *counts_host);
 
 /* Synchronises both streams, then copies the counters. */
 int moe_spec_stats(moe_spec_ctx *ctx, moe_spec_stats_t *out);

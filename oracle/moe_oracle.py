@@ -344,6 +344,10 @@ class MoEOracle:
         self.predict_signal = predict_signal
         # Est-PF / Hybrid-PF of Sec. 6: at the layers named here the prediction for layer l+1 comes from
         # the estimator's logits instead of layer l+1's router (all layers: Est-PF; some: Hybrid-PF)
+        # offline statistic of Sec. 3.1: running sum and count of the un-gated outputs of every executed
+        # expert; the per-expert default vector d_{l,e} is their mean (read it with default_vectors())
+        self.dacc_sum = np.zeros((model.n_layers, model.n_experts, model.hidden))
+        self.dacc_cnt = np.zeros((model.n_layers, model.n_experts), dtype=np.int64)
         self.estimator = estimator
         self.estimator_layers = set(estimator_layers or []) if estimator is not None else set()
         self.diag = [LayerDiagnostics(rank_match=[0] * model.top_k) for _ in range(model.n_layers)]
@@ -368,6 +372,10 @@ class MoEOracle:
         z = router_logits(m.router_w[layer], x)
         ids = topk_desc(z, m.top_k)
         return ids, gates_of(z, ids), _margin(z, m.top_k)
+
+    def default_vectors(self, layer: int):
+        """Mean un-gated output per expert over the steps that executed it (zero where never executed)."""
+        return self.dacc_sum[layer] / np.maximum(self.dacc_cnt[layer], 1)[:, None]
 
     def layer_step(self, layer: int, r) -> StepResult:
         m = self.m
@@ -446,7 +454,10 @@ class MoEOracle:
         for b in range(B):
             for j in range(k):
                 wg, wu, wd = m.expert_mats(layer, int(x_ids[b, j]))
-                out[b] += x_g[b, j] * expert_ffn(wg, wu, wd, s[b], self.bf16)
+                y = expert_ffn(wg, wu, wd, s[b], self.bf16)
+                out[b] += x_g[b, j] * y
+                self.dacc_sum[layer, int(x_ids[b, j])] += y
+                self.dacc_cnt[layer, int(x_ids[b, j])] += 1
 
         self.pending = None if n_ids is None else (n_ids, n_g)
         self.pending_signal = q_all

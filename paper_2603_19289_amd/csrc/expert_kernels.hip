@@ -375,6 +375,28 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
   }
 }
 
+// Default-vector statistics (paper: Sec. 3.1, the offline aggregation behind d_{l,e}): for every
+// position f routed to an expert of this launch, sum[e,:] += y[f,:] and cnt[e] += 1.
+__global__ __launch_bounds__(kBlock) void accumulate_defaults_kernel(const ExpertArgs a, const ActiveList act,
+                                                                     double *sum, unsigned long long *cnt) {
+  const int f = blockIdx.y;
+  const int e = a.exec_ids[f];
+  bool mine = false;
+  for (int i = 0; i < act.n; ++i) mine |= act.expert[i] == e;
+  if (!mine) return;
+  const int i = blockIdx.x * kBlock + threadIdx.x;
+  if (i < a.H) atomicAdd(sum + size_t(e) * a.H + i, double(a.y[size_t(f) * a.H + i]));
+  if (i == 0) atomicAdd(cnt + e, 1ull);
+}
+
+__global__ __launch_bounds__(kBlock) void default_means_kernel(const double *sum, const unsigned long long *cnt,
+                                                               float *mean, int H) {
+  const int e = blockIdx.y, i = blockIdx.x * kBlock + threadIdx.x;
+  if (i >= H) return;
+  const unsigned long long n = cnt[e];
+  mean[size_t(e) * H + i] = n ? float(sum[size_t(e) * H + i] / double(n)) : 0.f;
+}
+
 // O[b, i] = sum_j gates[b, j] * y[b, j, i]
 __global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
   const int i = blockIdx.x * kBlock + threadIdx.x;
@@ -561,6 +583,20 @@ hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st) {
     case 2: hipLaunchKernelGGL(gather_copy_kernel<2>, grid, block, 0, st, cl); break;
     default: hipLaunchKernelGGL(gather_copy_kernel<1>, grid, block, 0, st, cl); break;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate_defaults(const ExpertArgs &a, const ActiveList &act, double *sum,
+                                      unsigned long long *cnt, hipStream_t st) {
+  const dim3 grid((a.H + kBlock - 1) / kBlock, a.B * a.k), block(kBlock);
+  hipLaunchKernelGGL(accumulate_defaults_kernel, grid, block, 0, st, a, act, sum, cnt);
+  return hipGetLastError();
+}
+
+hipError_t launch_default_means(const double *sum, const unsigned long long *cnt, float *mean, int E, int H,
+                                hipStream_t st) {
+  const dim3 grid((H + kBlock - 1) / kBlock, E), block(kBlock);
+  hipLaunchKernelGGL(default_means_kernel, grid, block, 0, st, sum, cnt, mean, H);
   return hipGetLastError();
 }
 

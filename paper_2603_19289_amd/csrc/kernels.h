@@ -116,6 +116,12 @@ hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const 
                               hipStream_t st);
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);
 constexpr int kMfmaMinBatch = 16;     // decode batches from here on use the matrix-core expert kernels
+// Running sums for the default vectors: sum[e,:] += y[f,:] and cnt[e] += 1 for every position f whose
+// expert ids[f] is in the launch's active list; means = sum / max(cnt, 1).
+hipError_t launch_accumulate_defaults(const ExpertArgs &a, const ActiveList &act, double *sum,
+                                      unsigned long long *cnt, hipStream_t st);
+hipError_t launch_default_means(const double *sum, const unsigned long long *cnt, float *mean, int E, int H,
+                                hipStream_t st);
 bool b1_supported(int H, int dtype);
 hipError_t launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);

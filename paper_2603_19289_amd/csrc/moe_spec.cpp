@@ -42,7 +42,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, total;
+      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -94,6 +94,8 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.est_u = take(B * size_t(c->est_latent) * 8);
   a.est_t = take(B * size_t(c->est_ffn) * 8);
   a.est_v = take(B * size_t(c->est_latent) * 8);
+  a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
+  a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
   a.total = off;
   return a;
 }
@@ -421,6 +423,9 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   // counters start at zero
   if ((e = hipMemsetAsync(c->arena + lay.counter, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
+  if (cfg->accumulate_defaults) {
+    if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.total - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
+  }
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return bail(e, "synchronize");
   *out = c;
   return MOE_SPEC_OK;
@@ -687,7 +692,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   xa.B = batch; xa.k = k; xa.H = H; xa.I = I;
   xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
 
-  const bool fast_b1 = batch == 1 && b1_supported(H, cfg.dtype);
+  const bool fast_b1 = batch == 1 && b1_supported(H, cfg.dtype) && !cfg.accumulate_defaults;
   const bool use_mfma = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch;
 
   // --- cache waves: make resident (unless prefetched), wait, run
@@ -733,6 +738,11 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
       c->close_span(sp_gu, c->compute);
       if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
     }
+    if (cfg.accumulate_defaults &&
+        (e = launch_accumulate_defaults(xa, act, c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H,
+                                        c->at<unsigned long long>(c->lay.dacc_cnt) + size_t(layer) * E,
+                                        c->compute)) != hipSuccess)
+      return c->hip_fail(e, "default-vector accumulation");
     if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
     c->done_recorded[layer] = 1;
     c->st.hbm_bytes_algorithmic += int64_t(act.n) * int64_t(c->expert_bytes);
@@ -803,6 +813,25 @@ int moe_spec_layer_diagnostics(moe_spec_ctx *c, int layer, moe_spec_layer_diag_t
   return MOE_SPEC_OK;
 }
 
+int moe_spec_read_default_vectors(moe_spec_ctx *c, int layer, float *mean_dev, int64_t *counts_host) {
+  if (!c) return MOE_SPEC_EINVAL;
+  if (!c->cfg.accumulate_defaults) return c->fail(MOE_SPEC_ESTATE, "the context was created without accumulate_defaults");
+  if (layer < 0 || layer >= c->cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
+  if (!mean_dev) return c->fail(MOE_SPEC_EINVAL, "mean_dev is null");
+  const int E = c->cfg.n_experts, H = c->cfg.hidden;
+  const double *sum = c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H;
+  const unsigned long long *cnt = c->at<unsigned long long>(c->lay.dacc_cnt) + size_t(layer) * E;
+  hipError_t e = launch_default_means(sum, cnt, mean_dev, E, H, c->compute);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+  if (e != hipSuccess) return c->hip_fail(e, "default-vector means");
+  if (counts_host) {
+    static_assert(sizeof(unsigned long long) == sizeof(int64_t), "counter width");
+    if ((e = hipMemcpy(counts_host, cnt, size_t(E) * 8, hipMemcpyDeviceToHost)) != hipSuccess)
+      return c->hip_fail(e, "read counts");
+  }
+  return MOE_SPEC_OK;
+}
+
 int moe_spec_reset(moe_spec_ctx *c) {
   if (!c) return MOE_SPEC_EINVAL;
   hipError_t e = hipStreamSynchronize(c->compute);
@@ -818,6 +847,9 @@ int moe_spec_reset(moe_spec_ctx *c) {
   }
   if ((e = hipMemsetAsync(c->arena + c->lay.diag, 0, size_t(c->cfg.n_layers) * sizeof(LayerDiag), c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear counters");
+  if (c->cfg.accumulate_defaults &&
+      (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.total - c->lay.dacc_sum, c->compute)) != hipSuccess)
+    return c->hip_fail(e, "clear sums");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
   c->st = moe_spec_stats_t{};
   c->clock_running = false;

@@ -22,7 +22,7 @@ class Engine:
 
     def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
                  resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
-                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, estimator=None,
+                 predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, accumulate_defaults=0, estimator=None,
                  estimator_layers=None, device="cuda:0"):
         self.dev = torch.device(device)
         self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
@@ -34,7 +34,7 @@ class Engine:
                        dtype=M.BF16 if dtype == "bf16" else M.F32, mode=mode, rms_eps=rms_eps,
                        q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
                        profile=profile, copy_engine=copy_engine, predict_signal=predict_signal,
-                       diagnostics=diagnostics,
+                       diagnostics=diagnostics, accumulate_defaults=accumulate_defaults,
                        est_latent=0 if estimator is None else estimator["proj"].shape[0],
                        est_ffn=0 if estimator is None else estimator["ffn_in"].shape[0])
         need = M.moe_spec_arena_bytes(cfg)
@@ -118,6 +118,11 @@ class Engine:
 
     def layer_diagnostics(self, layer: int) -> dict:
         return M.moe_spec_layer_diagnostics(self.ctx, layer)
+
+    def read_default_vectors(self, layer: int):
+        mean = torch.empty((self.E, self.H), dtype=torch.float32, device=self.dev)
+        counts = M.moe_spec_read_default_vectors(self.ctx, layer, mean.data_ptr(), self.E)
+        return mean, counts
 
     def reset(self):
         M.moe_spec_reset(self.ctx)

@@ -23,6 +23,7 @@ class Config(C.Structure):
                 ("rms_eps", C.c_float), ("q_from_normalized", C.c_int32),
                 ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
                 ("predict_signal", C.c_int32), ("diagnostics", C.c_int32),
+                ("accumulate_defaults", C.c_int32), ("reserved0", C.c_int32),
                 ("est_latent", C.c_int32), ("est_ffn", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
@@ -80,6 +81,7 @@ def lib():
         L.moe_spec_layer_step.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
         L.moe_spec_stats.argtypes = [vp, C.POINTER(Stats)]
         L.moe_spec_layer_diagnostics.argtypes = [vp, i32, C.POINTER(LayerDiag)]
+        L.moe_spec_read_default_vectors.argtypes = [vp, i32, vp, C.POINTER(C.c_int64)]
         L.moe_spec_reset.argtypes = [vp]
         L.moe_spec_destroy.argtypes = [vp]
         L.moe_spec_destroy.restype = None
@@ -147,6 +149,12 @@ def moe_spec_layer_diagnostics(ctx, layer: int) -> dict:
     _check(lib().moe_spec_layer_diagnostics(ctx, layer, C.byref(d)), ctx)
     return {"predictions": d.predictions, "hits": d.hits, "rank_match": list(d.rank_match),
             "cos_sum": d.cos_sum, "cos_count": d.cos_count}
+
+
+def moe_spec_read_default_vectors(ctx, layer: int, mean_ptr, n_experts: int):
+    counts = (C.c_int64 * n_experts)()
+    _check(lib().moe_spec_read_default_vectors(ctx, layer, mean_ptr, counts), ctx)
+    return list(counts)
 
 
 def moe_spec_reset(ctx):

@@ -186,3 +186,38 @@ def test_per_layer_diagnostics_match_the_checker(signal, dtype, B):
     st = eng.stats()
     assert st["hits"] == orc.stats.hits and st["predictions"] == orc.stats.predictions
     eng.close()
+
+
+@pytest.mark.parametrize("dtype,B,mode", [("f32", 1, M.MODE_ON_DEMAND), ("bf16", 3, M.MODE_SPECULATIVE), ("bf16", 20, M.MODE_ON_DEMAND)])
+def test_accumulated_default_vectors_match_the_checker(dtype, B, mode):
+    # the offline statistic behind d_{l,e}: mean un-gated output per executed expert, with counts
+    wl = small_workload(n_layers=3, hidden=264, n_experts=12, top_k=3, inter=200, dtype=dtype, batch=B,
+                        tokens=5, slots=5, seed=61)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, mode, wl.slots)
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = _engine(wl, mode, res, ex, accumulate_defaults=1)
+    for t in range(wl.tokens):
+        eng.begin_token()
+        for l in range(wl.n_layers):
+            out, _ = eng.layer_step(l, torch.from_numpy(trace[t][l][0].astype(np.float32)).cuda())
+            torch.cuda.synchronize()
+            want = trace[t][l][1].out
+            assert (np.linalg.norm(out.cpu().numpy() - want, axis=-1) / np.linalg.norm(want, axis=-1)).max() < (2e-2 if dtype == "bf16" else 1e-5)
+    tol = 2e-2 if dtype == "bf16" else 1e-5
+    for l in range(wl.n_layers):
+        mean, counts = eng.read_default_vectors(l)
+        assert counts == orc.dacc_cnt[l].tolist()
+        got, want = mean.cpu().numpy().astype(np.float64), orc.default_vectors(l)
+        for e in range(wl.n_experts):
+            if counts[e]:
+                assert np.linalg.norm(got[e] - want[e]) <= tol * np.linalg.norm(want[e]), (l, e)
+            else:
+                assert not got[e].any()
+    eng.close()
+    # a context without the flag refuses
+    eng = _engine(wl, mode, res, ex)
+    buf = torch.empty((wl.n_experts, wl.hidden), device="cuda")
+    assert M.lib().moe_spec_read_default_vectors(eng.ctx, 0, buf.data_ptr(), None) == M.ESTATE
+    eng.close()

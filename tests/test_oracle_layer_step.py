@@ -276,3 +276,35 @@ def test_estimator_replaces_the_router_only_at_the_named_layers():
         z = O.estimator_logits(est, tr_h[t][1][1].q[0], 1)
         assert tr_h[t][1][1].next_ids[0].tolist() == O.topk_desc(z, wl.top_k).tolist()     # layer 1: estimator
     assert any(not np.array_equal(tr_h[t][1][1].next_ids, tr_p[t][1][1].next_ids) for t in range(wl.tokens))
+
+
+def test_accumulated_default_vectors_are_the_mean_expert_output_and_close_the_loop():
+    wl = small_workload(n_layers=3, dtype="f32", batch=2, tokens=6, slots=4)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    orc, tr = _run(model, wl, O.MODE_ON_DEMAND, x0, make_advance(wl, eps))
+    F = torch.nn.functional
+    for l in range(wl.n_layers):
+        acc = {}
+        for t in range(wl.tokens):
+            st = tr[t][l][1]
+            for b in range(wl.batch):
+                for j in range(wl.top_k):
+                    e = int(st.exec_ids[b, j])
+                    wg, wu, wd = (torch.from_numpy(O.decode_weights(m)) for m in model.expert_mats(l, e))
+                    s_ = torch.from_numpy(st.s[b])
+                    acc.setdefault(e, []).append(F.linear(F.silu(F.linear(s_, wg)) * F.linear(s_, wu), wd).numpy())
+        dv = orc.default_vectors(l)
+        for e in range(wl.n_experts):
+            want = np.mean(acc[e], axis=0) if e in acc else np.zeros(wl.hidden)
+            np.testing.assert_allclose(dv[e], want, rtol=1e-10, atol=1e-14)
+            assert orc.dacc_cnt[l, e] == len(acc.get(e, []))
+    # one token, no noise: the table collected on a first pass makes the prediction exact on a second pass
+    wl1 = small_workload(n_layers=4, dtype="f32", tokens=1, res_a=1.0, res_b=0.0)
+    res, ex, model = build(wl1, gains="random")
+    x0, _ = W.make_inputs(wl1)
+    adv = lambda t, l, r, out: r + out
+    first, _ = _run(model, wl1, O.MODE_ON_DEMAND, x0, adv)
+    model.dvecs = np.stack([first.default_vectors(l) for l in range(wl1.n_layers)])
+    second, _ = _run(model, wl1, O.MODE_SPECULATIVE, x0, adv)
+    assert second.stats.hits == second.stats.predictions > 0
