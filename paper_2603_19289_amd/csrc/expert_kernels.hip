@@ -10,8 +10,6 @@
 #include "device_utils.h"
 #include "kernels.h"
 
-#include <cstdlib>
-
 namespace moe_spec {
 namespace {
 
@@ -410,24 +408,22 @@ __global__ __launch_bounds__(kBlock) void combine_kernel(const ExpertArgs a) {
 
 // Host-to-device copy of whole expert blocks by a few workgroups that read the pinned pool
 // directly.  blockIdx.y picks the block, the workgroups of a row share it in 16-byte units.
-// UNROLL loads are in flight per lane; the launch keeps the bytes in flight near the link's
+// kCopyUnroll loads are in flight per lane; the launch keeps the bytes in flight near the link's
 // bandwidth-delay product, because host reads that queue up in the memory system delay the
 // HBM requests of kernels running beside the copy.
-template <int UNROLL>
+constexpr int kCopyWorkgroups = 16, kCopyUnroll = 2;      // 16 x 256 lanes x 2 x 16 B = 128 KB in flight
 __global__ __launch_bounds__(kBlock) void gather_copy_kernel(const CopyList cl) {
   const uint4 *src = static_cast<const uint4 *>(cl.src[blockIdx.y]);
   uint4 *dst = static_cast<uint4 *>(cl.dst[blockIdx.y]);
   const uint32_t n = cl.n16;
   const uint32_t stride = gridDim.x * kBlock;
   uint32_t i = blockIdx.x * kBlock + threadIdx.x;
-  if (UNROLL > 1) {
-    for (; i + (UNROLL - 1) * stride < n; i += UNROLL * stride) {
-      uint4 v[UNROLL];
+  for (; i + (kCopyUnroll - 1) * stride < n; i += kCopyUnroll * stride) {
+    uint4 v[kCopyUnroll];
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u) v[u] = src[i + u * stride];
+    for (int u = 0; u < kCopyUnroll; ++u) v[u] = src[i + u * stride];
 #pragma unroll
-      for (int u = 0; u < UNROLL; ++u) dst[i + u * stride] = v[u];
-    }
+    for (int u = 0; u < kCopyUnroll; ++u) dst[i + u * stride] = v[u];
   }
   for (; i < n; i += stride) dst[i] = src[i];
 }
@@ -481,8 +477,7 @@ hipError_t launch_down_t(const ExpertArgs &a, const ActiveList &act, hipStream_t
 template <typename WT, int NCH>
 void launch_gateup_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
   // one row per wavefront until that would exceed about 6144 wavefronts (24 per compute unit)
-  static const long target = getenv("MOE_SPEC_GU_WAVES") ? atol(getenv("MOE_SPEC_GU_WAVES")) : 6144;
-  long rpw = (long(a.I) * act.n + target - 1) / target;
+  long rpw = (long(a.I) * act.n + 6143) / 6144;
   if (rpw < 1) rpw = 1;
   const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
   hipLaunchKernelGGL((gateup_b1_kernel<WT, NCH>), grid, block, 0, st, a, act, int(rpw));
@@ -574,15 +569,8 @@ hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const ui
 
 hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st) {
   if (cl.n <= 0) return hipSuccess;
-  int total = cl.total_wgs > 0 ? cl.total_wgs : 32;
-  int wg_per_block = (total + cl.n - 1) / cl.n;
-  if (wg_per_block < 1) wg_per_block = 1;
-  const dim3 grid(wg_per_block, cl.n), block(kBlock);
-  switch (cl.unroll) {
-    case 4: hipLaunchKernelGGL(gather_copy_kernel<4>, grid, block, 0, st, cl); break;
-    case 2: hipLaunchKernelGGL(gather_copy_kernel<2>, grid, block, 0, st, cl); break;
-    default: hipLaunchKernelGGL(gather_copy_kernel<1>, grid, block, 0, st, cl); break;
-  }
+  const int wg_per_block = (kCopyWorkgroups + cl.n - 1) / cl.n;
+  hipLaunchKernelGGL(gather_copy_kernel, dim3(wg_per_block, cl.n), dim3(kBlock), 0, st, cl);
   return hipGetLastError();
 }
 

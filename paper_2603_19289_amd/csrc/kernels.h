@@ -92,7 +92,6 @@ struct CopyList {
   void *dst[kCopyListMax];         // device slot
   int32_t n;
   uint32_t n16;                    // 16-byte units per block
-  int32_t total_wgs, unroll;       // launch shape: workgroups over all blocks, loads in flight per lane
 };
 hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st);
 

@@ -16,7 +16,6 @@
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <deque>
 #include <new>
@@ -37,6 +36,8 @@ struct Pool {                       // one layer's slot cache (least recently us
   std::vector<int> slot_expert, slot_stamp, where;   // where[e] = slot or -1
   long clock = 0;
 };
+
+constexpr int kDmaQueues = 4;        // copy_engine 2: the caller's copy stream plus three more
 
 struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 gate/up kernel
 
@@ -110,8 +111,6 @@ struct moe_spec_ctx {
   hipStream_t compute = nullptr, copy = nullptr;
   std::vector<hipStream_t> copy_aux;             // owned; further DMA queues of copy_engine 2
   std::vector<hipEvent_t> aux_done;
-  int dma_queues = 4;
-  bool dma_split = false;                        // true: every expert cut in parts over all queues
 
   std::vector<const void *> router_w, gain, dvecs;
   struct { const void *proj, *layer_emb, *ffn_in, *ffn_out, *head; const float *ln_gain, *ln_bias; float ln_eps; bool set; } est{};
@@ -123,7 +122,6 @@ struct moe_spec_ctx {
   Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
   Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
   uint32_t seq = 0;
-  int copy_wgs = 16, copy_unroll = 2;   // gather-copy launch shape (see launch_gather_copy)
 
   // token state
   bool token_open = false;
@@ -222,7 +220,6 @@ struct moe_spec_ctx {
   int request(int layer, const std::vector<int> &experts, ActiveList *act, int *n_copies) {
     Pool &p = pools[layer];
     const int S = cfg.slots_per_layer;
-    p.clock += 1;
     std::vector<char> in_q(cfg.n_experts, 0);
     for (int e : experts) in_q[e] = 1;
     act->n = 0;
@@ -230,8 +227,10 @@ struct moe_spec_ctx {
     TimedSpan *span = nullptr;
     CopyList cl{};
     cl.n16 = uint32_t(expert_bytes / 16);
-    cl.total_wgs = copy_wgs;
-    cl.unroll = copy_unroll;
+    for (int e : experts)                        // refuse before any state changes
+      if (p.where[e] < 0 && !host_expert[size_t(layer) * cfg.n_experts + e])
+        return fail(MOE_SPEC_ESTATE, "expert %d of layer %d was never registered", e, layer);
+    p.clock += 1;
     for (int e : experts) {
       if (p.where[e] >= 0) { p.slot_stamp[p.where[e]] = int(p.clock); st.cache_hits += 1; }
     }
@@ -245,7 +244,6 @@ struct moe_spec_ctx {
       }
       if (victim < 0) return fail(MOE_SPEC_ESTATE, "no evictable slot (request larger than the pool)");
       const char *src = host_expert[size_t(layer) * cfg.n_experts + e];
-      if (!src) return fail(MOE_SPEC_ESTATE, "expert %d of layer %d was never registered", e, layer);
       if (copies == 0) {
         if (done_recorded[layer]) {
           hipError_t w = hipStreamWaitEvent(copy, done[layer], 0);
@@ -276,17 +274,10 @@ struct moe_spec_ctx {
           cl.n = 0;
         }
       } else if (cfg.copy_engine == MOE_SPEC_COPY_DMA2) {
-        const size_t nq = 1 + copy_aux.size();
-        const size_t part = (expert_bytes / nq) & ~size_t(255);
-        hipError_t c = hipSuccess;
-        if (!dma_split) {                            // whole experts, round-robin over the queues
-          const size_t q = size_t(copies) % nq;
-          c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
-        } else
-        for (size_t q = 0; q < nq && c == hipSuccess; ++q) {
-          const size_t off = q * part, len = q + 1 == nq ? expert_bytes - off : part;
-          c = hipMemcpyAsync(dst + off, src + off, len, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
-        }
+        // whole experts, dealt round-robin over the queues (cutting every expert into one part per
+        // queue moved no more bytes per second and made the timing erratic)
+        const size_t q = size_t(copies) % (1 + copy_aux.size());
+        hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
         if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
       } else {
         hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, copy);
@@ -371,8 +362,6 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   c->expert_bytes = expert_bytes_of(cfg);
   c->slot_stride = align_up(c->expert_bytes, 256);
   c->arena = static_cast<char *>(cfg->device_arena);
-  if (const char *v = getenv("MOE_SPEC_COPY_WGS")) c->copy_wgs = std::max(1, atoi(v));        // tuning knobs
-  if (const char *v = getenv("MOE_SPEC_COPY_UNROLL")) c->copy_unroll = std::max(1, atoi(v));
   c->compute = static_cast<hipStream_t>(cfg->compute_stream);
   c->copy = static_cast<hipStream_t>(cfg->copy_stream);
   const int L = cfg->n_layers, E = cfg->n_experts, S = cfg->slots_per_layer;
@@ -398,9 +387,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
     if ((e = hipEventCreateWithFlags(&c->done[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
   if (cfg->copy_engine == MOE_SPEC_COPY_DMA2) {
-    if (const char *v = getenv("MOE_SPEC_DMA_QUEUES")) c->dma_queues = std::min(8, std::max(2, atoi(v)));
-    if (const char *v = getenv("MOE_SPEC_DMA_SPLIT")) c->dma_split = atoi(v) != 0;
-    for (int q = 1; q < c->dma_queues; ++q) {
+    for (int q = 1; q < kDmaQueues; ++q) {
       hipStream_t sq = nullptr;
       hipEvent_t ev = nullptr;
       if ((e = hipStreamCreateWithFlags(&sq, hipStreamNonBlocking)) != hipSuccess) return bail(e, "auxiliary copy stream");
