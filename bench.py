@@ -185,7 +185,8 @@ def main():
     #      mean launch duration inside the two instrumented token loops (event pairs on the compute stream);
     #      the same kernels timed back to back on cold slots, without the token loop, are listed beside it
     kern = {}
-    for which, name in ((0, "expert_gateup_gemv"), (1, "expert_down_combine_gemv"), (2, "router")):
+    for which, name in ((0, "expert_gateup_gemv"), (3, "pure_read_of_the_same_bytes"), (1, "expert_down_combine_gemv"),
+                        (2, "router")):
         ms, nbytes = prof_eng.time_kernel(which, args.kernel_reps)
         kern[name] = {"us_per_launch": ms * 1e3, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
     prof_eng.close()

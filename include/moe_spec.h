@@ -199,7 +199,8 @@ const char *moe_spec_last_error(const moe_spec_ctx *ctx);
 /* Measurement aid: launches one of the weight-streaming kernels `reps` times back to back on the
  * compute stream between two timing events, each launch on the slots of the next layer in turn
  * (so that no launch finds its weights in a cache), executing k resident slots per launch for a
- * batch of one.  which: 0 = gate/up GEMV + SwiGLU, 1 = down GEMV, 2 = router (true routing).
+ * batch of one.  which: 0 = gate/up GEMV + SwiGLU, 1 = down GEMV + combine, 2 = router (true routing),
+ * 3 = a kernel that only reads the gate/up bytes of the same slots (what streaming alone reaches).
  * Writes the mean milliseconds per launch and the weight bytes one launch reads.
  * The slot contents are whatever the cache holds; outputs go to scratch. */
 int moe_spec_time_kernel(moe_spec_ctx *ctx, int which, int reps, double *ms_per_launch,

@@ -37,6 +37,32 @@ __device__ __forceinline__ void load_chunk(const WT *p, float (&f)[Packed<WT>::N
   Packed<WT>::unpack(*reinterpret_cast<const typename Packed<WT>::Raw *>(p), f);
 }
 
+// Dot product of one packed weight chunk with one packed activation chunk of the same dtype,
+// added to acc in float.  bf16: four two-element dot instructions per 16 bytes (both operands
+// stay packed; every product is exact in float).  float: four multiply-adds.
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+__device__ __forceinline__ float dot2_bf16(uint32_t w, uint32_t a, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w), __builtin_bit_cast(bf16x2_t, a), acc, false);
+}
+
+__device__ __forceinline__ float dot_chunk(const uint4 &w, const uint4 &a, float acc) {
+  acc = dot2_bf16(w.x, a.x, acc);
+  acc = dot2_bf16(w.y, a.y, acc);
+  acc = dot2_bf16(w.z, a.z, acc);
+  return dot2_bf16(w.w, a.w, acc);
+}
+
+__device__ __forceinline__ float dot_chunk(const float4 &w, const float4 &a, float acc) {
+  acc += w.x * a.x;
+  acc += w.y * a.y;
+  acc += w.z * a.z;
+  return acc + w.w * a.w;
+}
+
+__device__ __forceinline__ void zero_chunk(uint4 &v) { v = make_uint4(0u, 0u, 0u, 0u); }
+__device__ __forceinline__ void zero_chunk(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
+
 // float -> nearest bfloat16 (ties to even) -> float; finite inputs.
 __device__ __forceinline__ float round_to_bf16(float x) {
   uint32_t u = __float_as_uint(x);

@@ -259,13 +259,7 @@ __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArg
     const char *base = a.pool + size_t(act.slot[j]) * a.slot_bytes + down_off;
     const typename R::Raw w = *reinterpret_cast<const typename R::Raw *>(base + size_t(c) * sizeof(WT));
     const typename R::Raw hh = *reinterpret_cast<const typename R::Raw *>(hq + size_t(j) * I + c);
-    float fw[VN], fh[VN];
-    R::unpack(w, fw);
-    R::unpack(hh, fh);
-    float part = 0.f;
-#pragma unroll
-    for (int x = 0; x < VN; ++x) part += fw[x] * fh[x];
-    acc += a.exec_gates[j] * part;
+    acc += a.exec_gates[j] * dot_chunk(w, hh, 0.f);
   }
   const float v = wave_sum(acc);
   if (lane == 0) a.out[row] = v;
@@ -393,6 +387,20 @@ __global__ __launch_bounds__(kBlock) void default_means_kernel(const double *sum
   if (i >= H) return;
   const unsigned long long n = cnt[e];
   mean[size_t(e) * H + i] = n ? float(sum[size_t(e) * H + i] / double(n)) : 0.f;
+}
+
+// Measurement aid: reads the gate/up matrices of the launch's slots and does nothing else (the
+// sum is never stored unless it hits an impossible value).  What a kernel can reach on these bytes.
+__global__ __launch_bounds__(kBlock) void stream_read_kernel(const ExpertArgs a, const ActiveList act, float *sink) {
+  const uint4 *p = reinterpret_cast<const uint4 *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
+  const size_t n16 = size_t(2) * a.I * a.H * (a.bf16 ? 2 : 4) / 16;
+  const size_t stride = size_t(gridDim.x) * kBlock;
+  float acc = 0.f;
+  for (size_t i = size_t(blockIdx.x) * kBlock + threadIdx.x; i < n16; i += stride) {
+    const uint4 v = p[i];
+    acc += __uint_as_float(v.x ^ v.y ^ v.z ^ v.w);
+  }
+  if (acc == 1.2345e-30f) *sink = acc;
 }
 
 // O[b, i] = sum_j gates[b, j] * y[b, j, i]
@@ -585,6 +593,11 @@ hipError_t launch_default_means(const double *sum, const unsigned long long *cnt
                                 hipStream_t st) {
   const dim3 grid((H + kBlock - 1) / kBlock, E), block(kBlock);
   hipLaunchKernelGGL(default_means_kernel, grid, block, 0, st, sum, cnt, mean, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(768, act.n), dim3(kBlock), 0, st, a, act, a.out);
   return hipGetLastError();
 }
 

@@ -111,6 +111,7 @@ hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_combine(const ExpertArgs &a, hipStream_t st);
+hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, hipStream_t st);
 hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
                               hipStream_t st);
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);

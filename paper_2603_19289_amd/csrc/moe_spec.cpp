@@ -849,7 +849,7 @@ int moe_spec_reset(moe_spec_ctx *c) {
 
 int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_launch, int64_t *bytes_per_launch) {
   if (!c) return MOE_SPEC_EINVAL;
-  if (which < 0 || which > 2 || reps < 1 || !ms_per_launch || !bytes_per_launch)
+  if (which < 0 || which > 3 || reps < 1 || !ms_per_launch || !bytes_per_launch)
     return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
   const moe_spec_config &cfg = c->cfg;
   const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter;
@@ -893,6 +893,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
       xa.pool = c->pool_base(l);
       if (which == 0) le = fast ? launch_gateup_b1(xa, act, cfg.dtype, c->compute) : launch_gateup(xa, act, cfg.dtype, c->compute);
       else if (which == 1) le = fast ? launch_down_combine_b1(xa, act, cfg.dtype, c->compute) : launch_down(xa, act, cfg.dtype, c->compute);
+      else if (which == 3) le = launch_stream_read(xa, act, c->compute);
       else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
     }
     if (pass == 1 && le == hipSuccess) le = hipEventRecord(t1, c->compute);
@@ -905,7 +906,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   if (le != hipSuccess) return c->hip_fail(le, "kernel launch");
   if (e != hipSuccess) return c->hip_fail(e, "timing");
   *ms_per_launch = double(ms) / reps;
-  *bytes_per_launch = which == 0 ? int64_t(k) * 2 * I * H * wbytes
+  *bytes_per_launch = which == 0 || which == 3 ? int64_t(k) * 2 * I * H * wbytes
                     : which == 1 ? int64_t(k) * I * H * wbytes
                                  : int64_t(E) * H * wbytes;
   return MOE_SPEC_OK;
