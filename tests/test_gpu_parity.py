@@ -113,7 +113,19 @@ def test_edge_shapes(mode):
     run_teacher_forced(small_workload(name="one_expert", n_experts=1, top_k=1, slots=1, tokens=3), MODES[mode])
     run_teacher_forced(small_workload(name="one_layer", n_layers=1, tokens=3), MODES[mode])
     run_teacher_forced(small_workload(name="wide_router", n_experts=200, top_k=16, slots=16, tokens=2, hidden=128), MODES[mode])
+    run_teacher_forced(small_workload(name="max_inter", n_layers=2, hidden=64, inter=32768, n_experts=2, top_k=1, slots=1,
+                                      batch=2, tokens=1), MODES[mode])       # 128 KB of LDS in the down kernel
     run_teacher_forced(small_workload(name="max_batch", batch=64, n_experts=16, top_k=2, slots=8, tokens=2, dtype="f32"), MODES[mode])
+
+
+@pytest.mark.parametrize("dtype,H", [("bf16", 4608), ("f32", 4352), ("bf16", 8192), ("f32", 8192)])
+def test_wide_hidden_sizes_take_the_streaming_fallbacks(dtype, H):
+    # beyond 64*8 register chunks per lane the routing kernel streams its row in a loop; float32 rows
+    # beyond 4096 columns leave the register-resident batch-1 expert kernel for the LDS-staged one;
+    # 8192 is the largest hidden size the library accepts (64 KB of float64 LDS per token)
+    wl = small_workload(name="wide", n_layers=3, hidden=H, n_experts=6, top_k=2, inter=72, dtype=dtype,
+                        batch=1, tokens=2, slots=3, seed=71)
+    run_teacher_forced(wl, O.MODE_SPECULATIVE)
 
 
 @pytest.mark.parametrize("mode", list(MODES))
