@@ -84,7 +84,8 @@ typedef struct {
                                        un-gated outputs of every executed expert (the offline statistic
                                        behind the default vectors, Sec. 3.1); costs L*E*H doubles of arena
                                        and disables the fused batch-1 down+combine kernel */
-  int32_t reserved0;
+  int32_t max_prefill_tokens;       /* P_max >= 0: most prompt tokens one moe_spec_prefill_layer_step takes;
+                                       0: no prefill path.  Costs about P_max*(k+2)*H floats of arena */
   int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
                                        feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
@@ -107,6 +108,7 @@ typedef struct {
   double  gateup_ms;                /* profile=1 only: summed duration of the gate/up expert kernel
                                        launches, each bracketed by two events on the compute stream */
   int64_t gateup_launches;
+  int64_t prefill_tokens;           /* prompt tokens through moe_spec_prefill_layer_step, summed over layers */
 } moe_spec_stats_t;
 
 /* Optional per-step outputs, each dev [B, k] or NULL.  ids are by descending logit. */
@@ -164,6 +166,20 @@ int moe_spec_begin_token(moe_spec_ctx *ctx);
  * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host. */
 int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
                         const moe_spec_step_outputs *outs);
+
+/* Prefill (paper: Sec. 5.2, prefill phase): one MoE block over all n_tokens prompt tokens at once.
+ * Nothing is predicted: a prompt activates (nearly) every expert, so every expert of `layer` is
+ * streamed from the host pool through the layer's slots, half of the slots receiving the next group
+ * of experts while the kernels run on the other half, and every token executes its true top-k
+ * experts.  Copies depend on no routing result, so the copy stream runs ahead of the compute stream
+ * into the following layers' calls (the layer-ahead loading of the paper); the call never blocks.
+ * r_dev [n_tokens,H] float, out_dev [n_tokens,H] float (valid in compute-stream order),
+ * 1 <= n_tokens <= max_prefill_tokens (MOE_SPEC_EINVAL otherwise).  true_ids / true_gates: dev
+ * [n_tokens,k] or NULL.  Any layer order; not between begin_token and a token's last layer_step
+ * (MOE_SPEC_ESTATE).  Leaves the layer's slot cache empty.  Counts E cache misses and E expert
+ * blocks of host-to-device traffic. */
+int moe_spec_prefill_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int n_tokens,
+                                void *out_dev, int32_t *true_ids, float *true_gates);
 
 /* Statistics of the predictions made FOR one layer (at the layer before it): recall@k as in the
  * paper's per-layer hit-rate figure, agreement per routing-weight rank as in its rank-alignment

@@ -377,6 +377,31 @@ class MoEOracle:
         """Mean un-gated output per expert over the steps that executed it (zero where never executed)."""
         return self.dacc_sum[layer] / np.maximum(self.dacc_cnt[layer], 1)[:, None]
 
+    def prefill_layer_step(self, layer: int, r) -> StepResult:
+        """Prefill (Sec. 5.2): all prompt tokens at once.  Nothing is predicted: with enough tokens every
+        expert is active, so every expert of the layer is loaded (streamed one layer ahead) and the true
+        router-selected experts are executed, i.e. the standard MoE block.  Traffic: E experts per layer.
+        The layer's pool is left empty for the decode cache."""
+        m = self.m
+        r = np.asarray(r, dtype=np.float64)
+        P, k = r.shape[0], m.top_k
+        out = np.zeros((P, m.hidden))
+        s = np.zeros((P, m.hidden))
+        ids = np.zeros((P, k), dtype=np.int64)
+        g = np.zeros((P, k))
+        margin = np.zeros(P)
+        for b in range(P):
+            sb = rmsnorm(r[b], m.rms_gain[layer], m.rms_eps)
+            s[b] = bf16_round(sb) if self.bf16 else sb
+            ids[b], g[b], margin[b] = self.route(layer, s[b])
+            for j in range(k):
+                out[b] += g[b, j] * expert_ffn(*m.expert_mats(layer, int(ids[b, j])), s[b], self.bf16)
+        self.pools[layer] = LRUPool(self.S)
+        self.stats.cache_misses += m.n_experts
+        self.stats.h2d_bytes += m.n_experts * m.expert_bytes
+        self.stats.layer_steps += 1
+        return StepResult(out, ids, g, ids.copy(), g.copy(), None, None, margin, None, s, None)
+
     def layer_step(self, layer: int, r) -> StepResult:
         m = self.m
         if layer != self.next_layer:

@@ -43,7 +43,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, total;
+      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, pf_s, pf_sq, pf_ids, pf_gates, pf_y, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -65,6 +65,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->predict_signal != 0 && c->predict_signal != 1) return "unknown predict_signal";
   if (c->est_latent < 0 || c->est_ffn < 0 || (c->est_latent == 0) != (c->est_ffn == 0)) return "estimator sizes must both be set or both be 0";
   if (c->est_latent % 8 || c->est_ffn % 8) return "estimator sizes must be multiples of 8";
+  if (c->max_prefill_tokens < 0 || c->max_prefill_tokens > 65536) return "max_prefill_tokens out of range";
   if (c->est_latent > MOE_SPEC_MAX_HIDDEN || c->est_ffn > 8 * MOE_SPEC_MAX_HIDDEN) return "estimator sizes too large";
   return nullptr;
 }
@@ -97,6 +98,12 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.est_v = take(B * size_t(c->est_latent) * 8);
   a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
   a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
+  const size_t P = size_t(c->max_prefill_tokens);
+  a.pf_s = take(P * H * 4);
+  a.pf_sq = take(P * H * 2);
+  a.pf_ids = take(P * k * 4);
+  a.pf_gates = take(P * k * 4);
+  a.pf_y = take(P * k * H * 4);
   a.total = off;
   return a;
 }
@@ -111,6 +118,7 @@ struct moe_spec_ctx {
   hipStream_t compute = nullptr, copy = nullptr;
   std::vector<hipStream_t> copy_aux;             // owned; further DMA queues of copy_engine 2
   std::vector<hipEvent_t> aux_done;
+  hipEvent_t pf_ready[2] = {nullptr, nullptr}, pf_done[2] = {nullptr, nullptr};   // prefill: one pair per half pool
 
   std::vector<const void *> router_w, gain, dvecs;
   struct { const void *proj, *layer_emb, *ffn_in, *ffn_out, *head; const float *ln_gain, *ln_bias; float ln_eps; bool set; } est{};
@@ -214,6 +222,50 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
 
+  // One expert block host -> device by the configured engine; `index` counts the blocks of the
+  // current group (it picks the queue).  copy_join ends the group: afterwards everything issued is
+  // ordered before whatever is recorded next on the copy stream.
+  int copy_expert(CopyList &cl, int index, char *dst, const char *src) {
+    if (cfg.copy_engine == MOE_SPEC_COPY_KERNEL) {
+      cl.src[cl.n] = src;
+      cl.dst[cl.n] = dst;
+      if (++cl.n == kCopyListMax) {
+        hipError_t c = launch_gather_copy(cl, copy);
+        if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
+        cl.n = 0;
+      }
+    } else if (cfg.copy_engine == MOE_SPEC_COPY_DMA2) {
+      // whole experts, dealt round-robin over the queues (cutting every expert into one part per
+      // queue moved no more bytes per second and made the timing erratic)
+      const size_t q = size_t(index) % (1 + copy_aux.size());
+      hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
+      if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
+    } else {
+      hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, copy);
+      if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
+    }
+    return MOE_SPEC_OK;
+  }
+  int copy_join(CopyList &cl) {
+    if (cl.n > 0) {
+      hipError_t c = launch_gather_copy(cl, copy);
+      if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
+      cl.n = 0;
+    }
+    for (size_t q = 0; q < copy_aux.size(); ++q) {
+      hipError_t r = hipEventRecord(aux_done[q], copy_aux[q]);
+      if (r == hipSuccess) r = hipStreamWaitEvent(copy, aux_done[q], 0);
+      if (r != hipSuccess) return hip_fail(r, "join copy queues");
+    }
+    return MOE_SPEC_OK;
+  }
+  // Every copy queue waits for an event recorded on the compute stream.
+  int copy_queues_wait(hipEvent_t ev) {
+    hipError_t w = hipStreamWaitEvent(copy, ev, 0);
+    for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, ev, 0);
+    return w == hipSuccess ? MOE_SPEC_OK : hip_fail(w, "copy stream wait");
+  }
+
   // Cache request for at most S experts (ascending ids): hits are stamped, each miss takes the
   // least recently used slot that holds no requested expert and is copied in on the copy stream.
   // Fills act with (expert, slot) of every requested expert.  Returns the number of copies issued.
@@ -265,38 +317,13 @@ struct moe_spec_ctx {
       p.slot_stamp[victim] = int(p.clock);
       p.where[e] = victim;
       char *dst = pool_base(layer) + size_t(victim) * slot_stride;
-      if (cfg.copy_engine == MOE_SPEC_COPY_KERNEL) {
-        cl.src[cl.n] = src;
-        cl.dst[cl.n] = dst;
-        if (++cl.n == kCopyListMax) {
-          hipError_t c = launch_gather_copy(cl, copy);
-          if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
-          cl.n = 0;
-        }
-      } else if (cfg.copy_engine == MOE_SPEC_COPY_DMA2) {
-        // whole experts, dealt round-robin over the queues (cutting every expert into one part per
-        // queue moved no more bytes per second and made the timing erratic)
-        const size_t q = size_t(copies) % (1 + copy_aux.size());
-        hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, q == 0 ? copy : copy_aux[q - 1]);
-        if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
-      } else {
-        hipError_t c = hipMemcpyAsync(dst, src, expert_bytes, hipMemcpyHostToDevice, copy);
-        if (c != hipSuccess) return hip_fail(c, "host-to-device expert copy");
-      }
+      if (int rc = copy_expert(cl, copies, dst, src)) return rc;
       copies += 1;
       st.cache_misses += 1;
       st.h2d_bytes += int64_t(expert_bytes);
     }
-    if (cl.n > 0) {
-      hipError_t c = launch_gather_copy(cl, copy);
-      if (c != hipSuccess) return hip_fail(c, "host-to-device gather copy");
-    }
     if (copies > 0) {                            // the request is complete when every queue is
-      for (size_t q = 0; q < copy_aux.size(); ++q) {
-        hipError_t r = hipEventRecord(aux_done[q], copy_aux[q]);
-        if (r == hipSuccess) r = hipStreamWaitEvent(copy, aux_done[q], 0);
-        if (r != hipSuccess) return hip_fail(r, "join copy queues");
-      }
+      if (int rc = copy_join(cl)) return rc;
     }
     if (copies > 0) {
       close_span(span, copy);
@@ -386,6 +413,10 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
     if ((e = hipEventCreateWithFlags(&c->ready[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
     if ((e = hipEventCreateWithFlags(&c->done[l], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
+  for (int h = 0; h < 2 && cfg->max_prefill_tokens > 0; ++h) {
+    if ((e = hipEventCreateWithFlags(&c->pf_ready[h], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+    if ((e = hipEventCreateWithFlags(&c->pf_done[h], hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
+  }
   if (cfg->copy_engine == MOE_SPEC_COPY_DMA2) {
     for (int q = 1; q < kDmaQueues; ++q) {
       hipStream_t sq = nullptr;
@@ -427,6 +458,10 @@ void moe_spec_destroy(moe_spec_ctx *c) {
   }
   for (hipStream_t q : c->copy_aux) (void)hipStreamDestroy(q);
   for (hipEvent_t ev : c->aux_done) (void)hipEventDestroy(ev);
+  for (int h = 0; h < 2; ++h) {
+    if (c->pf_ready[h]) (void)hipEventDestroy(c->pf_ready[h]);
+    if (c->pf_done[h]) (void)hipEventDestroy(c->pf_done[h]);
+  }
   for (auto ev : c->ready) if (ev) (void)hipEventDestroy(ev);
   for (auto ev : c->done) if (ev) (void)hipEventDestroy(ev);
   for (auto &sp : c->spans) { (void)hipEventDestroy(sp.a); (void)hipEventDestroy(sp.b); }
@@ -760,6 +795,151 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   c->next_layer = layer + 1;
   if (last) c->token_open = false;
   c->st.layer_steps += 1;
+  return MOE_SPEC_OK;
+}
+
+int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int n_tokens, void *out_dev,
+                                int32_t *true_ids, float *true_gates) {
+  if (!c) return MOE_SPEC_EINVAL;
+  const moe_spec_config &cfg = c->cfg;
+  if (!r_dev || !out_dev) return c->fail(MOE_SPEC_EINVAL, "null activation pointer");
+  if (cfg.max_prefill_tokens < 1) return c->fail(MOE_SPEC_ESTATE, "context was created without a prefill path");
+  if (n_tokens < 1 || n_tokens > cfg.max_prefill_tokens)
+    return c->fail(MOE_SPEC_EINVAL, "n_tokens %d out of range", n_tokens);
+  if (layer < 0 || layer >= cfg.n_layers) return c->fail(MOE_SPEC_EINVAL, "layer %d out of range", layer);
+  if (c->token_open) return c->fail(MOE_SPEC_ESTATE, "prefill inside a decode step");
+  if (!c->router_w[layer]) return c->fail(MOE_SPEC_ESTATE, "resident tables of layer %d were never set", layer);
+  const int E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter, S = cfg.slots_per_layer;
+  for (int x = 0; x < E; ++x)
+    if (!c->host_expert[size_t(layer) * E + x])
+      return c->fail(MOE_SPEC_ESTATE, "expert %d of layer %d was never registered", x, layer);
+  const int P = n_tokens, MB = cfg.max_batch;
+  const int halves = S >= 2 ? 2 : 1;
+  const int group = std::min(S / halves, E);           // experts per group; group g lives in half g % halves
+  const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
+  const float *r = static_cast<const float *>(r_dev);
+  float *out = static_cast<float *>(out_dev);
+  float *s_all = c->at<float>(c->lay.pf_s);
+  uint16_t *sq_all = c->at<uint16_t>(c->lay.pf_sq);
+  int32_t *ids_all = c->at<int32_t>(c->lay.pf_ids);
+  float *gates_all = c->at<float>(c->lay.pf_gates);
+  float *y_all = c->at<float>(c->lay.pf_y);
+  hipError_t e;
+  if (!c->clock_running) { c->clock_running = true; c->t0 = std::chrono::steady_clock::now(); }
+
+  // --- true routing of every prompt token, one kernel per micro-batch of at most max_batch tokens
+  TimedSpan *sp_route = c->open_span(0, c->compute);
+  for (int t0 = 0; t0 < P; t0 += MB) {
+    const int nb = std::min(MB, P - t0);
+    RouteArgs ra{};
+    ra.r = r + size_t(t0) * H;
+    ra.w = c->router_w[layer];
+    ra.gain = static_cast<const float *>(c->gain[layer]);
+    ra.z = c->at<double>(c->lay.z);
+    ra.counter = c->at<unsigned int>(c->lay.counter);
+    ra.vec_out = s_all + size_t(t0) * H;
+    ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 && nb >= kMfmaMinBatch ? sq_all + size_t(t0) * H : nullptr;
+    ra.ids_out = ids_all + size_t(t0) * k;
+    ra.gates_out = gates_all + size_t(t0) * k;
+    ra.diag = c->at<LayerDiag>(c->lay.diag) + layer;
+    ra.user_ids = true_ids ? true_ids + size_t(t0) * k : nullptr;
+    ra.user_gates = true_gates ? true_gates + size_t(t0) * k : nullptr;
+    ra.seq = ++c->seq;
+    ra.B = nb; ra.H = H; ra.E = E; ra.k = k;
+    ra.eps = cfg.rms_eps;
+    ra.bf16 = cfg.dtype == MOE_SPEC_BF16;
+    if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+    c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
+  }
+  c->close_span(sp_route, c->compute);
+
+  // --- the pool is taken over: whatever the decode cache held is dropped
+  Pool &p = c->pools[layer];
+  std::fill(p.slot_expert.begin(), p.slot_expert.end(), -1);
+  std::fill(p.slot_stamp.begin(), p.slot_stamp.end(), 0);
+  std::fill(p.where.begin(), p.where.end(), -1);
+  if (c->done_recorded[layer]) { int rc = c->copy_queues_wait(c->done[layer]); if (rc) return rc; }
+  if (c->ready_recorded[layer]) {
+    for (hipStream_t q : c->copy_aux)
+      if ((e = hipStreamWaitEvent(q, c->ready[layer], 0)) != hipSuccess) return c->hip_fail(e, "copy queue wait");
+  }
+
+  // --- stream every expert through the two halves of the pool
+  for (int e0 = 0, g = 0; e0 < E; e0 += group, ++g) {
+    const int half = g % halves, n_here = std::min(group, E - e0);
+    if (g >= halves) { int rc = c->copy_queues_wait(c->pf_done[half]); if (rc) return rc; }
+    TimedSpan *sp_copy = c->open_span(1, c->copy);
+    CopyList cl{};
+    cl.n16 = uint32_t(c->expert_bytes / 16);
+    ActiveList act{};
+    for (int x = 0; x < n_here; ++x) {
+      const int slot = half * group + x;               // < halves * group <= S
+      int rc = c->copy_expert(cl, x, c->pool_base(layer) + size_t(slot) * c->slot_stride,
+                              c->host_expert[size_t(layer) * E + e0 + x]);
+      if (rc) return rc;
+      act.expert[x] = int16_t(e0 + x);
+      act.slot[x] = int16_t(slot);
+    }
+    act.n = n_here;
+    if (int rc = c->copy_join(cl)) return rc;
+    c->close_span(sp_copy, c->copy);
+    if ((e = hipEventRecord(c->pf_ready[half], c->copy)) != hipSuccess) return c->hip_fail(e, "record ready event");
+    c->st.cache_misses += n_here;
+    c->st.h2d_bytes += int64_t(n_here) * int64_t(c->expert_bytes);
+
+    TimedSpan *sp_stall = c->open_span(2, c->compute);
+    if ((e = hipStreamWaitEvent(c->compute, c->pf_ready[half], 0)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
+    c->close_span(sp_stall, c->compute);
+    TimedSpan *sp_exec = c->open_span(0, c->compute);
+    for (int t0 = 0; t0 < P; t0 += MB) {
+      const int nb = std::min(MB, P - t0);
+      ExpertArgs xa{};
+      xa.pool = c->pool_base(layer);
+      xa.slot_bytes = c->slot_stride;
+      xa.s = s_all + size_t(t0) * H;
+      xa.exec_ids = ids_all + size_t(t0) * k;
+      xa.exec_gates = gates_all + size_t(t0) * k;
+      xa.h = c->at<float>(c->lay.h);                   // [nb,k,I], reused by every micro-batch
+      xa.y = y_all + size_t(t0) * k * H;
+      xa.out = out + size_t(t0) * H;
+      xa.B = nb; xa.k = k; xa.H = H; xa.I = I;
+      xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
+      if (cfg.dtype == MOE_SPEC_BF16 && nb >= kMfmaMinBatch) {
+        uint16_t *hq = c->at<uint16_t>(c->lay.h);
+        if ((e = launch_gateup_mfma(xa, act, sq_all + size_t(t0) * H, hq, c->compute)) != hipSuccess)
+          return c->hip_fail(e, "gate/up MFMA kernel");
+        if ((e = launch_down_mfma(xa, act, hq, c->compute)) != hipSuccess) return c->hip_fail(e, "down MFMA kernel");
+      } else {
+        if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
+        if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+      }
+      if (cfg.accumulate_defaults &&
+          (e = launch_accumulate_defaults(xa, act, c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H,
+                                          c->at<unsigned long long>(c->lay.dacc_cnt) + size_t(layer) * E,
+                                          c->compute)) != hipSuccess)
+        return c->hip_fail(e, "default-vector accumulation");
+      c->st.hbm_bytes_algorithmic += int64_t(n_here) * int64_t(c->expert_bytes);
+    }
+    c->close_span(sp_exec, c->compute);
+    if ((e = hipEventRecord(c->pf_done[half], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
+  }
+
+  // --- gate-weighted sums
+  TimedSpan *sp_comb = c->open_span(0, c->compute);
+  for (int t0 = 0; t0 < P; t0 += MB) {
+    ExpertArgs xa{};
+    xa.exec_gates = gates_all + size_t(t0) * k;
+    xa.y = y_all + size_t(t0) * k * H;
+    xa.out = out + size_t(t0) * H;
+    xa.B = std::min(MB, P - t0); xa.k = k; xa.H = H; xa.I = I;
+    if ((e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
+  }
+  c->close_span(sp_comb, c->compute);
+  // later copies into this pool wait for the kernels above
+  if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
+  c->done_recorded[layer] = 1;
+  c->st.layer_steps += 1;
+  c->st.prefill_tokens += P;
   return MOE_SPEC_OK;
 }
 

@@ -23,7 +23,7 @@ class Engine:
     def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
                  resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
                  predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, accumulate_defaults=0, estimator=None,
-                 estimator_layers=None, device="cuda:0"):
+                 estimator_layers=None, max_prefill_tokens=0, device="cuda:0"):
         self.dev = torch.device(device)
         self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
         self.max_batch = max_batch
@@ -35,6 +35,7 @@ class Engine:
                        q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
                        profile=profile, copy_engine=copy_engine, predict_signal=predict_signal,
                        diagnostics=diagnostics, accumulate_defaults=accumulate_defaults,
+                       max_prefill_tokens=max_prefill_tokens,
                        est_latent=0 if estimator is None else estimator["proj"].shape[0],
                        est_ffn=0 if estimator is None else estimator["ffn_in"].shape[0])
         need = M.moe_spec_arena_bytes(cfg)
@@ -105,6 +106,23 @@ class Engine:
             self.compute.wait_stream(torch.cuda.current_stream(self.dev))
         M.moe_spec_layer_step(self.ctx, layer, r.data_ptr(), B, out.data_ptr(), outs)
         return out, bufs
+
+    def prefill_layer_step(self, layer: int, r: torch.Tensor, out: Optional[torch.Tensor] = None, want_ids=False,
+                           sync_input=True):
+        """r: [P,H] float32 on the device, all prompt tokens of one layer."""
+        P = r.shape[0]
+        assert r.dtype == torch.float32 and r.is_contiguous() and r.shape[1] == self.H
+        if out is None:
+            out = torch.empty_like(r)
+        ids = gates = None
+        if want_ids:
+            ids = torch.full((P, self.k), -1, dtype=torch.int32, device=self.dev)
+            gates = torch.full((P, self.k), float("nan"), dtype=torch.float32, device=self.dev)
+        if sync_input:
+            self.compute.wait_stream(torch.cuda.current_stream(self.dev))
+        M.moe_spec_prefill_layer_step(self.ctx, layer, r.data_ptr(), P, out.data_ptr(),
+                                      ids.data_ptr() if want_ids else None, gates.data_ptr() if want_ids else None)
+        return out, ids, gates
 
     def advance(self, r, out, eps, a, b, r_next=None):
         if r_next is None:

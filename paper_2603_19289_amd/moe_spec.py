@@ -23,7 +23,7 @@ class Config(C.Structure):
                 ("rms_eps", C.c_float), ("q_from_normalized", C.c_int32),
                 ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
                 ("predict_signal", C.c_int32), ("diagnostics", C.c_int32),
-                ("accumulate_defaults", C.c_int32), ("reserved0", C.c_int32),
+                ("accumulate_defaults", C.c_int32), ("max_prefill_tokens", C.c_int32),
                 ("est_latent", C.c_int32), ("est_ffn", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
@@ -34,7 +34,8 @@ class Stats(C.Structure):
                 ("hits", C.c_int64), ("cache_hits", C.c_int64), ("cache_misses", C.c_int64),
                 ("h2d_bytes", C.c_int64), ("hbm_bytes_algorithmic", C.c_int64),
                 ("copy_ms", C.c_double), ("compute_ms", C.c_double), ("stall_ms", C.c_double),
-                ("wall_ms", C.c_double), ("gateup_ms", C.c_double), ("gateup_launches", C.c_int64)]
+                ("wall_ms", C.c_double), ("gateup_ms", C.c_double), ("gateup_launches", C.c_int64),
+                ("prefill_tokens", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -79,6 +80,7 @@ def lib():
         L.moe_spec_set_estimator_layers.argtypes = [vp, C.POINTER(C.c_uint8), i32]
         L.moe_spec_begin_token.argtypes = [vp]
         L.moe_spec_layer_step.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
+        L.moe_spec_prefill_layer_step.argtypes = [vp, i32, vp, i32, vp, vp, vp]
         L.moe_spec_stats.argtypes = [vp, C.POINTER(Stats)]
         L.moe_spec_layer_diagnostics.argtypes = [vp, i32, C.POINTER(LayerDiag)]
         L.moe_spec_read_default_vectors.argtypes = [vp, i32, vp, C.POINTER(C.c_int64)]
@@ -136,6 +138,10 @@ def moe_spec_begin_token(ctx):
 def moe_spec_layer_step(ctx, layer, r_ptr, batch, out_ptr, outs: Optional[StepOutputs] = None):
     _check(lib().moe_spec_layer_step(ctx, layer, r_ptr, batch, out_ptr,
                                      C.byref(outs) if outs is not None else None), ctx)
+
+
+def moe_spec_prefill_layer_step(ctx, layer, r_ptr, n_tokens, out_ptr, true_ids_ptr=None, true_gates_ptr=None):
+    _check(lib().moe_spec_prefill_layer_step(ctx, layer, r_ptr, n_tokens, out_ptr, true_ids_ptr, true_gates_ptr), ctx)
 
 
 def moe_spec_stats(ctx) -> dict:

@@ -1,0 +1,153 @@
+"""GPU parity of the prefill step (Sec. 5.2, prefill phase): all prompt tokens of a layer at once, every
+expert streamed through the layer's slots, true routing executed.  Against the CPU checker on the same
+seeded inputs: ids equal, gates to float32 rounding, outputs within 1e-5 (float32) / 2e-2 (bf16), and
+the transfer counters equal (E expert blocks per layer)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import moe_oracle as O
+from paper_2603_19289_amd import moe_spec as M
+from paper_2603_19289_amd import workload as W
+from tests.helpers import build, make_advance, small_workload
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+def rel_err(got, want):
+    return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
+
+
+def prompt_of(wl, P):
+    """[P,H] first-layer residuals and [L,P,H] noise for the layer-to-layer update, from the seeded generators."""
+    x0, eps = W.make_inputs(dataclasses.replace(wl, batch=P), tokens=1)
+    return x0[0], eps[0]
+
+
+def run_prefill(wl, P, max_batch, label, **engine_kw):
+    from paper_2603_19289_amd.engine import engine_for
+    print(f"[case] prefill {label} L={wl.n_layers} H={wl.hidden} E={wl.n_experts} k={wl.top_k} I={wl.inter} "
+          f"P={P} micro-batch={max_batch} S={wl.slots} {wl.dtype} {engine_kw}", flush=True)
+    res, ex, model = build(wl, "random")
+    r_np, eps = prompt_of(wl, P)
+    orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
+    eng = engine_for(wl, O.MODE_SPECULATIVE, res, ex, max_batch=max_batch, max_prefill_tokens=P + 3, **engine_kw)
+    worst = 0.0
+    try:
+        for l in range(wl.n_layers):
+            want = orc.prefill_layer_step(l, r_np)
+            r = torch.from_numpy(r_np.astype(np.float32)).to("cuda")
+            out, ids, gates = eng.prefill_layer_step(l, r, want_ids=True)
+            torch.cuda.synchronize()
+            np.testing.assert_array_equal(ids.cpu().numpy(), want.true_ids, err_msg=f"layer {l}")
+            np.testing.assert_allclose(gates.cpu().numpy(), want.true_gates, atol=2e-7, rtol=1e-6, err_msg=f"layer {l}")
+            err = rel_err(out.cpu().numpy().astype(np.float64), want.out).max()
+            worst = max(worst, err)
+            assert err <= TOL[wl.dtype], f"layer {l}: relative error {err:.3e}"
+            r_np = W.advance_residual(wl, r_np, want.out, eps[l])
+        st = eng.stats()
+        for name in ("layer_steps", "cache_hits", "cache_misses", "h2d_bytes", "predictions"):
+            assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
+        assert st["prefill_tokens"] == P * wl.n_layers
+    finally:
+        eng.close()
+    print(f"[ok] worst relative error {worst:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("copy_engine", [M.COPY_DMA, M.COPY_KERNEL, M.COPY_DMA2])
+def test_prefill_fp32_ragged_micro_batches(copy_engine):
+    wl = small_workload(n_layers=2, dtype="f32", slots=4)           # groups of 2 experts, 4 groups per layer
+    run_prefill(wl, P=37, max_batch=16, label="f32", copy_engine=copy_engine)
+
+
+def test_prefill_bf16_matrix_core_and_generic_tail():
+    wl = small_workload(n_layers=2, hidden=128, n_experts=16, top_k=4, inter=96, dtype="bf16", slots=5)
+    run_prefill(wl, P=100, max_batch=32, label="bf16 odd S", copy_engine=M.COPY_DMA2)   # 32+32+32+4 tokens
+
+
+def test_prefill_bf16_small_micro_batch():
+    wl = small_workload(n_layers=1, hidden=128, n_experts=16, top_k=4, inter=96, dtype="bf16", slots=8)
+    run_prefill(wl, P=19, max_batch=8, label="bf16 generic", copy_engine=M.COPY_DMA)
+
+
+def test_prefill_single_slot_and_single_token():
+    wl = small_workload(n_layers=2, top_k=1, slots=1, dtype="f32")  # one slot: copy and compute alternate
+    run_prefill(wl, P=5, max_batch=4, label="S=1", copy_engine=M.COPY_DMA2)
+    run_prefill(small_workload(n_layers=1, dtype="f32"), P=1, max_batch=1, label="P=1", copy_engine=M.COPY_DMA)
+
+
+def test_prefill_pool_larger_than_expert_count():
+    wl = small_workload(n_layers=1, dtype="bf16", slots=40)         # both halves hold all 8 experts: one group
+    run_prefill(wl, P=21, max_batch=16, label="S>2E", copy_engine=M.COPY_KERNEL)
+
+
+@pytest.mark.parametrize("mode", [O.MODE_SPECULATIVE, O.MODE_ON_DEMAND])
+def test_decode_after_prefill_starts_from_an_empty_cache(mode):
+    """Prefill over every layer, then decode steps: ids, outputs and cache counters follow the checker,
+    whose pools are empty after its prefill."""
+    from paper_2603_19289_amd.engine import engine_for
+    wl = small_workload(n_layers=3, dtype="bf16", batch=2, tokens=3, slots=4)
+    res, ex, model = build(wl, "random")
+    P = 11
+    r_np, eps_p = prompt_of(wl, P)
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, mode, wl.slots)
+    eng = engine_for(wl, mode, res, ex, max_batch=4, max_prefill_tokens=P, copy_engine=M.COPY_DMA2)
+    try:
+        # a few decode steps first so that the pools hold something the prefill must drop
+        warm = O.run_tokens(orc, x0[:1], make_advance(wl, eps))
+        eng.begin_token()
+        for l in range(wl.n_layers):
+            eng.layer_step(l, torch.from_numpy(warm[0][l][0].astype(np.float32)).to("cuda"))
+        for l in range(wl.n_layers):
+            want = orc.prefill_layer_step(l, r_np)
+            out, _, _ = eng.prefill_layer_step(l, torch.from_numpy(r_np.astype(np.float32)).to("cuda"))
+            torch.cuda.synchronize()
+            assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL["bf16"]
+            r_np = W.advance_residual(wl, r_np, want.out, eps_p[l])
+        trace = O.run_tokens(orc, x0[1:], lambda t, l, r, out: W.advance_residual(wl, r, out, eps[t + 1, l]))
+        for t in range(len(trace)):
+            eng.begin_token()
+            for l in range(wl.n_layers):
+                r_l, want = trace[t][l]
+                out, ids = eng.layer_step(l, torch.from_numpy(r_l.astype(np.float32)).to("cuda"), want_ids=True)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), want.exec_ids)
+                assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL["bf16"]
+        st = eng.stats()
+        for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes"):
+            assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
+    finally:
+        eng.close()
+
+
+def test_prefill_argument_and_state_errors():
+    from paper_2603_19289_amd.engine import engine_for
+    wl = small_workload(n_layers=2, dtype="f32")
+    res, ex, _ = build(wl)
+    r = torch.zeros((4, wl.hidden), dtype=torch.float32, device="cuda")
+    eng = engine_for(wl, O.MODE_SPECULATIVE, res, ex, max_batch=2, max_prefill_tokens=3)
+    try:
+        with pytest.raises(M.MoeSpecError) as ei:
+            eng.prefill_layer_step(0, r)                        # 4 tokens > 3
+        assert ei.value.code == M.EINVAL
+        with pytest.raises(M.MoeSpecError) as ei:
+            eng.prefill_layer_step(2, r[:2].contiguous())       # no such layer
+        assert ei.value.code == M.EINVAL
+        eng.begin_token()
+        with pytest.raises(M.MoeSpecError) as ei:
+            eng.prefill_layer_step(0, r[:2].contiguous())       # inside a decode step
+        assert ei.value.code == M.ESTATE
+    finally:
+        eng.close()
+    eng = engine_for(wl, O.MODE_SPECULATIVE, res, ex, max_batch=2)
+    try:
+        with pytest.raises(M.MoeSpecError) as ei:
+            eng.prefill_layer_step(0, r[:2].contiguous())       # created without a prefill path
+        assert ei.value.code == M.ESTATE
+    finally:
+        eng.close()

@@ -308,3 +308,19 @@ def test_accumulated_default_vectors_are_the_mean_expert_output_and_close_the_lo
     model.dvecs = np.stack([first.default_vectors(l) for l in range(wl1.n_layers)])
     second, _ = _run(model, wl1, O.MODE_SPECULATIVE, x0, adv)
     assert second.stats.hits == second.stats.predictions > 0
+
+
+def test_prefill_is_the_standard_block_on_every_token_and_loads_every_expert():
+    wl = small_workload(n_layers=2, dtype="bf16", batch=7, tokens=1, slots=4)
+    res, ex, model = build(wl, gains="random")
+    x0, _ = W.make_inputs(wl)
+    pre = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
+    ond = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots)
+    ond.begin_token()
+    a = pre.prefill_layer_step(0, x0[0])
+    b = ond.layer_step(0, x0[0])
+    np.testing.assert_array_equal(a.out, b.out)                 # same arithmetic as a decode step on the true experts
+    np.testing.assert_array_equal(a.true_ids, b.true_ids)
+    assert pre.stats.cache_misses == wl.n_experts and pre.stats.h2d_bytes == wl.n_experts * wl.expert_bytes
+    assert pre.stats.predictions == 0
+    assert pre.pools[0].slot_expert == [-1] * wl.slots          # nothing is kept for the decode cache
