@@ -45,6 +45,8 @@ def parse():
                         "state and for the baseline signal s_l (the statistics of the paper's per-layer figures)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
+    p.add_argument("--prefill", type=int, default=0, metavar="P",
+                   help="also time the prefill step on a prompt of P tokens (every expert of every layer streamed)")
     p.add_argument("--kernel-reps", type=int, default=480)
     p.add_argument("--copy-engine", choices=["auto", "kernel", "dma", "dma2"], default="auto",
                    help="auto: each mode gets the engine that is fastest for it (speculative: four DMA queues, "
@@ -217,6 +219,43 @@ def main():
                 "cosine_to_next_router_input_per_layer": [round(d["cos_sum"] / d["cos_count"], 4) if d["cos_count"] else None for d in per],
                 "top_rank_agreement_per_layer": [round(d["rank_match"][0] / d["cos_count"], 4) if d["cos_count"] else None for d in per]}
 
+    # ---- prefill (Sec. 5.2, prefill phase): all prompt tokens per layer, every expert streamed layer-ahead
+    prefill = None
+    if args.prefill > 0:
+        import dataclasses
+        P = args.prefill
+        px0, peps = W.make_inputs(dataclasses.replace(wl, batch=P), tokens=1)
+        pr0 = torch.from_numpy(px0[0]).to(dev)
+        pe = torch.from_numpy(peps[0]).to(dev)
+        name = spec_auto if args.copy_engine == "auto" else args.copy_engine
+        eng = engine_for(wl, M.MODE_SPECULATIVE, res, pool, copy_engine=codes[name], max_batch=min(64, P),
+                         max_prefill_tokens=P)
+        pout = torch.empty((P, H), dtype=torch.float32, device=dev)
+        pbuf = [torch.empty((P, H), dtype=torch.float32, device=dev) for _ in range(2)]
+
+        def prompt_pass():
+            with torch.cuda.stream(eng.compute):
+                r = pr0
+                for l in range(L):
+                    eng.prefill_layer_step(l, r, pout, sync_input=False)
+                    if l + 1 < L:
+                        r = eng.advance(r, pout, pe[l], wl.res_a, wl.res_b, pbuf[l & 1])
+        prompt_pass()
+        torch.cuda.synchronize()
+        before = eng.stats()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            prompt_pass()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 2
+        after = eng.stats()
+        eng.close()
+        nbytes = (after["h2d_bytes"] - before["h2d_bytes"]) / 2
+        prefill = {"prompt_tokens": P, "micro_batch": min(64, P), "copy_engine": name, "ms_per_prompt": dt * 1e3,
+                   "ms_per_layer": dt * 1e3 / L, "prompt_tokens_per_s": P / dt, "h2d_gb_per_prompt": nbytes / 1e9,
+                   "h2d_gbs_wall": nbytes / dt / 1e9, "link_frac_wall_nominal": nbytes / dt / 1e9 / LINK_PEAK_GBS}
+        log(f"[bench] prefill P={P}: {dt * 1e3:.1f} ms per prompt, {dt * 1e3 / L:.2f} ms per layer, H2D {nbytes / dt / 1e9:.2f} GB/s")
+
     if args.calibrate_copy:
         a = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         b = torch.empty_like(a)
@@ -261,6 +300,7 @@ def main():
         "link": {"peak_nominal_gbs": LINK_PEAK_GBS, "achieved_gbs_speculative_wall": spec["h2d_gbs_wall"],
                  "achieved_gbs_on_demand_wall": ond["h2d_gbs_wall"]},
         "roofline": roofline, "cpu_baseline": cpu, "signal_diagnostics": diagnostics,
+        "prefill": prefill,
     }
     print(json.dumps(line), flush=True)
 

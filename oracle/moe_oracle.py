@@ -394,8 +394,18 @@ class MoEOracle:
             sb = rmsnorm(r[b], m.rms_gain[layer], m.rms_eps)
             s[b] = bf16_round(sb) if self.bf16 else sb
             ids[b], g[b], margin[b] = self.route(layer, s[b])
+        y = np.zeros((P, k, m.hidden))
+        for e in range(m.n_experts):              # expert by expert, so that each is decoded once
+            where = np.argwhere(ids == e)
+            if len(where):
+                mats = m.expert_mats(layer, e)
+                for b, j in where:
+                    y[b, j] = expert_ffn(*mats, s[b], self.bf16)
+                    self.dacc_sum[layer, e] += y[b, j]        # statistic behind the default vectors (Sec. 3.1)
+                    self.dacc_cnt[layer, e] += 1
+        for b in range(P):
             for j in range(k):
-                out[b] += g[b, j] * expert_ffn(*m.expert_mats(layer, int(ids[b, j])), s[b], self.bf16)
+                out[b] += g[b, j] * y[b, j]
         self.pools[layer] = LRUPool(self.S)
         self.stats.cache_misses += m.n_experts
         self.stats.h2d_bytes += m.n_experts * m.expert_bytes

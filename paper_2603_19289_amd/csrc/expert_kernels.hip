@@ -284,8 +284,19 @@ __device__ __forceinline__ bf16x8_t load_bf16x8(const uint16_t *p, bool valid) {
   return __builtin_bit_cast(bf16x8_t, v);
 }
 
-// GATEUP: hq[f, row] = bf16(silu(W_gate[row,:] . s_b) * (W_up[row,:] . s_b)),  act_q = s_l as bf16 [B, K]
-// else  : y[f, row]  = W_down[row,:] . hq[f,:],                                  act_q = hq [B*k, K]
+// One step of the reduction for one wavefront: the weight fragments of its 16 rows and the token
+// fragments of up to NT tiles, each the 2 x 16 bytes a lane feeds to two MFMAs.
+template <bool GATEUP, int NT>
+struct MfmaStep {
+  bf16x8_t w0[2], w1[2];       // rows of W_gate (or W_down), rows of W_up
+  bf16x8_t x[NT][2];
+};
+
+// GATEUP: hq[f, row] = bf16(silu(W_gate[row,:] . s_b) * (W_up[row,:] . s_b)),  act_q = s_l as bf16 [tokens, K]
+// else  : y[f, row]  = W_down[row,:] . hq[f,:],                                  act_q = hq [tokens*k, K]
+// The positions f = b*k + j routed to the expert come either from the [B,k] id table of a decode
+// batch (B <= 64, one grid plane) or, with a.pos_list, from per-expert lists over any number of
+// tokens, 64 positions per grid plane blockIdx.z.
 template <bool GATEUP, int NT>
 __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a, const ActiveList act,
                                                              const uint16_t *act_q, uint16_t *hq_out) {
@@ -298,8 +309,17 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
 
   const int e = act.expert[blockIdx.y];
   const uint16_t *wbase = reinterpret_cast<const uint16_t *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
-  gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
-  const int n = n_list;
+  int n;
+  if (a.pos_list) {
+    const int first = blockIdx.z * kMaxBatch;
+    n = min(kMaxBatch, a.pos_count[e] - first);
+    if (n <= 0) return;                        // the same for the whole workgroup
+    if (tid < n) list[tid] = a.pos_list[size_t(e) * a.list_stride + first + tid];
+    __syncthreads();
+  } else {
+    gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
+    n = n_list;
+  }
   const int row_base = (blockIdx.x * kWaves + wave) * 16;
   if (row_base >= R || n == 0) return;
   const int ntiles = (n + 15) / 16;
@@ -320,25 +340,42 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
 #pragma unroll
   for (int t = 0; t < NT; ++t) { acc0[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; acc1[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  for (int k0 = 0; k0 < K; k0 += 64) {
+  // columns past K load nothing and contribute zeros, so the two-stage loop below may run one
+  // step beyond the end
+  auto fetch = [&](int k0, MfmaStep<GATEUP, NT> &st) {
     const int kk = k0 + 16 * g;
     const bool v0 = kk < K, v1 = kk + 8 < K;
-    const bf16x8_t a00 = load_bf16x8(p0 + kk, v0), a01 = load_bf16x8(p0 + kk + 8, v1);
-    bf16x8_t a10 = a00, a11 = a01;
-    if (GATEUP) { a10 = load_bf16x8(p1 + kk, v0); a11 = load_bf16x8(p1 + kk + 8, v1); }
+    st.w0[0] = load_bf16x8(p0 + kk, v0);
+    st.w0[1] = load_bf16x8(p0 + kk + 8, v1);
+    if (GATEUP) { st.w1[0] = load_bf16x8(p1 + kk, v0); st.w1[1] = load_bf16x8(p1 + kk + 8, v1); }
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       if (t < ntiles) {
-        const bf16x8_t b0 = load_bf16x8(bp[t] + kk, v0 && bvalid[t]);
-        const bf16x8_t b1 = load_bf16x8(bp[t] + kk + 8, v1 && bvalid[t]);
-        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a00, b0, acc0[t], 0, 0, 0);
-        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a01, b1, acc0[t], 0, 0, 0);
+        st.x[t][0] = load_bf16x8(bp[t] + kk, v0 && bvalid[t]);
+        st.x[t][1] = load_bf16x8(bp[t] + kk + 8, v1 && bvalid[t]);
+      }
+    }
+  };
+  auto multiply = [&](const MfmaStep<GATEUP, NT> &st) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (t < ntiles) {
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w0[0], st.x[t][0], acc0[t], 0, 0, 0);
+        acc0[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w0[1], st.x[t][1], acc0[t], 0, 0, 0);
         if (GATEUP) {
-          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a10, b0, acc1[t], 0, 0, 0);
-          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a11, b1, acc1[t], 0, 0, 0);
+          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w1[0], st.x[t][0], acc1[t], 0, 0, 0);
+          acc1[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(st.w1[1], st.x[t][1], acc1[t], 0, 0, 0);
         }
       }
     }
+  };
+  MfmaStep<GATEUP, NT> even, odd;              // the loads of one step are in flight during the other's MFMAs
+  fetch(0, even);
+  for (int k0 = 0; k0 < K; k0 += 128) {
+    fetch(k0 + 64, odd);
+    multiply(even);
+    fetch(k0 + 128, even);
+    multiply(odd);
   }
 
   const int r0 = row_base + 4 * g;             // this lane's four output rows, all inside or all outside
@@ -365,6 +402,34 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
       }
     }
   }
+}
+
+// Positions f = b*k + j of an id table [tokens, k], grouped by expert, ascending inside a group:
+// pos[e*stride + i] for i < count[e].  One workgroup per expert; each wavefront counts and then
+// writes its own contiguous quarter of the table.
+__global__ __launch_bounds__(kBlock) void expert_lists_kernel(const int32_t *ids, int n_ids, int stride,
+                                                              int32_t *pos, int32_t *count) {
+  __shared__ int wave_count[kWaves];
+  const int e = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int per_wave = (n_ids + kBlock - 1) / kBlock * kWave;
+  const int lo = wave * per_wave, hi = min(n_ids, lo + per_wave);
+  int c = 0;
+  for (int base = lo; base < hi; base += kWave) {
+    const int f = base + lane;
+    c += __popcll(__ballot(f < hi && ids[f] == e));
+  }
+  if (lane == 0) wave_count[wave] = c;
+  __syncthreads();
+  int off = 0, total = 0;
+  for (int w = 0; w < kWaves; ++w) { if (w < wave) off += wave_count[w]; total += wave_count[w]; }
+  for (int base = lo; base < hi; base += kWave) {
+    const int f = base + lane;
+    const bool match = f < hi && ids[f] == e;
+    const unsigned long long mask = __ballot(match);
+    if (match) pos[size_t(e) * stride + off + __popcll(mask & ((1ull << lane) - 1ull))] = f;
+    off += __popcll(mask);
+  }
+  if (tid == 0) count[e] = total;
 }
 
 // Default-vector statistics (paper: Sec. 3.1, the offline aggregation behind d_{l,e}): for every
@@ -517,8 +582,9 @@ template <bool GATEUP>
 hipError_t launch_expert_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *act_q, uint16_t *hq,
                               hipStream_t st) {
   const int rows = GATEUP ? a.I : a.H;
-  const dim3 grid((rows + 16 * kWaves - 1) / (16 * kWaves), act.n), block(kBlock);
-  const int nt = (a.B + 15) / 16;
+  const int planes = a.pos_list ? (a.list_tokens + kMaxBatch - 1) / kMaxBatch : 1;
+  const dim3 grid((rows + 16 * kWaves - 1) / (16 * kWaves), act.n, planes), block(kBlock);
+  const int nt = a.pos_list ? (std::min(a.list_tokens, kMaxBatch) + 15) / 16 : (a.B + 15) / 16;
   switch (nt) {
     case 1: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 1>), grid, block, 0, st, a, act, act_q, hq); break;
     case 2: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 2>), grid, block, 0, st, a, act, act_q, hq); break;
@@ -573,6 +639,12 @@ hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const 
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st) {
   if (act.n <= 0) return hipSuccess;
   return launch_expert_mfma<false>(a, act, hq, nullptr, st);
+}
+
+hipError_t launch_expert_lists(const int32_t *ids, int tokens, int k, int E, int32_t *pos, int32_t *count,
+                               hipStream_t st) {
+  hipLaunchKernelGGL(expert_lists_kernel, dim3(E), dim3(kBlock), 0, st, ids, tokens * k, tokens, pos, count);
+  return hipGetLastError();
 }
 
 hipError_t launch_gather_copy(const CopyList &cl, hipStream_t st) {

@@ -47,7 +47,7 @@ struct RouteArgs {
   const int32_t *d_ids;       // spec: [B,k] true ids of layer l
   const double *d_gates;      // spec: [B,k] true gates of layer l
   double *z;                  // [B,E] logits scratch
-  unsigned int *counter;      // arrival counter, zero between launches
+  unsigned int *counter;      // [1 + kMaxBatch] arrival counters (groups done, then one per token group), zero between launches
   float *vec_out;             // [B,H] normalised (and rounded) vector, or null
   uint16_t *vec_out_q;        // [B,H] the same as bf16 bit patterns (bf16 mode), or null
   int32_t *ids_out;           // [B,k]
@@ -83,6 +83,11 @@ struct ExpertArgs {
   float *y;                   // [B,k,H] un-gated expert outputs
   float *out;                 // [B,H]
   int B, k, H, I, bf16, tok_tile;
+  // matrix-core kernels over more than one decode batch (prefill): positions grouped by expert as
+  // written by launch_expert_lists for list_tokens tokens; null: the [B,k] table exec_ids is searched
+  const int32_t *pos_list;    // [E, list_stride]
+  const int32_t *pos_count;   // [E]
+  int list_stride, list_tokens;
 };
 
 // Host-to-device gather copy: each entry moves one expert block from the pinned pool to a slot.
@@ -115,6 +120,8 @@ hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, hipStr
 hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
                               hipStream_t st);
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);
+hipError_t launch_expert_lists(const int32_t *ids, int tokens, int k, int E, int32_t *pos, int32_t *count,
+                               hipStream_t st);      // pos [E, tokens], count [E]
 constexpr int kMfmaMinBatch = 16;     // decode batches from here on use the matrix-core expert kernels
 // Running sums for the default vectors: sum[e,:] += y[f,:] and cnt[e] += 1 for every position f whose
 // expert ids[f] is in the launch's active list; means = sum / max(cnt, 1).

@@ -43,7 +43,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, pf_s, pf_sq, pf_ids, pf_gates, pf_y, total;
+      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -82,7 +82,7 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.slots = take(size_t(c->n_layers) * c->slots_per_layer * align_up(expert_bytes_of(c), 256));
   a.s_buf = take(B * H * 4);
   a.z = take(B * E * 8);
-  a.counter = take(256);
+  a.counter = take((1 + kMaxBatch) * sizeof(unsigned int));
   a.true_ids = take(B * k * 4);
   a.true_gates = take(B * k * 4);
   a.true_gates64 = take(B * k * 8);
@@ -104,6 +104,9 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.pf_ids = take(P * k * 4);
   a.pf_gates = take(P * k * 4);
   a.pf_y = take(P * k * H * 4);
+  a.pf_hq = take(c->dtype == MOE_SPEC_BF16 ? P * k * I * 2 : 0);
+  a.pf_pos = take(c->dtype == MOE_SPEC_BF16 ? E * P * 4 : 0);
+  a.pf_count = take(c->dtype == MOE_SPEC_BF16 && P ? E * 4 : 0);
   a.total = off;
   return a;
 }
@@ -439,7 +442,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   c->mb_true_dev = static_cast<Mailbox *>(mb_dev);
   c->mb_next_dev = c->mb_true_dev + 1;
   // counters start at zero
-  if ((e = hipMemsetAsync(c->arena + lay.counter, 0, 256, c->compute)) != hipSuccess) return bail(e, "clear counter");
+  if ((e = hipMemsetAsync(c->arena + lay.counter, 0, (1 + kMaxBatch) * sizeof(unsigned int), c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
   if (cfg->accumulate_defaults) {
     if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.total - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
@@ -838,7 +841,7 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
     ra.z = c->at<double>(c->lay.z);
     ra.counter = c->at<unsigned int>(c->lay.counter);
     ra.vec_out = s_all + size_t(t0) * H;
-    ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 && nb >= kMfmaMinBatch ? sq_all + size_t(t0) * H : nullptr;
+    ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 ? sq_all + size_t(t0) * H : nullptr;
     ra.ids_out = ids_all + size_t(t0) * k;
     ra.gates_out = gates_all + size_t(t0) * k;
     ra.diag = c->at<LayerDiag>(c->lay.diag) + layer;
@@ -851,13 +854,19 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
     if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
     c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
   }
+  const bool all_at_once = cfg.dtype == MOE_SPEC_BF16;   // matrix-core kernels over per-expert position lists
+  if (all_at_once &&
+      (e = launch_expert_lists(ids_all, P, k, E, c->at<int32_t>(c->lay.pf_pos), c->at<int32_t>(c->lay.pf_count),
+                               c->compute)) != hipSuccess)
+    return c->hip_fail(e, "expert list kernel");
   c->close_span(sp_route, c->compute);
 
   // --- the pool is taken over: whatever the decode cache held is dropped
   Pool &p = c->pools[layer];
   std::fill(p.slot_expert.begin(), p.slot_expert.end(), -1);
-  std::fill(p.slot_stamp.begin(), p.slot_stamp.end(), 0);
+  std::fill(p.slot_stamp.begin(), p.slot_stamp.end(), -1);
   std::fill(p.where.begin(), p.where.end(), -1);
+  p.clock = 0;
   if (c->done_recorded[layer]) { int rc = c->copy_queues_wait(c->done[layer]); if (rc) return rc; }
   if (c->ready_recorded[layer]) {
     for (hipStream_t q : c->copy_aux)
@@ -891,8 +900,10 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
     if ((e = hipStreamWaitEvent(c->compute, c->pf_ready[half], 0)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
     c->close_span(sp_stall, c->compute);
     TimedSpan *sp_exec = c->open_span(0, c->compute);
-    for (int t0 = 0; t0 < P; t0 += MB) {
-      const int nb = std::min(MB, P - t0);
+    // bf16: the matrix-core kernels take all tokens of every expert in one launch, 64 per grid plane;
+    // float32: the general kernels, one launch pair per micro-batch
+    for (int t0 = 0; t0 < P; t0 += all_at_once ? P : MB) {
+      const int nb = all_at_once ? std::min(MB, P) : std::min(MB, P - t0);
       ExpertArgs xa{};
       xa.pool = c->pool_base(layer);
       xa.slot_bytes = c->slot_stride;
@@ -904,20 +915,30 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
       xa.out = out + size_t(t0) * H;
       xa.B = nb; xa.k = k; xa.H = H; xa.I = I;
       xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
-      if (cfg.dtype == MOE_SPEC_BF16 && nb >= kMfmaMinBatch) {
-        uint16_t *hq = c->at<uint16_t>(c->lay.h);
-        if ((e = launch_gateup_mfma(xa, act, sq_all + size_t(t0) * H, hq, c->compute)) != hipSuccess)
+      if (all_at_once) {
+        uint16_t *hq = c->at<uint16_t>(c->lay.pf_hq);  // [P,k,I]
+        xa.pos_list = c->at<int32_t>(c->lay.pf_pos);
+        xa.pos_count = c->at<int32_t>(c->lay.pf_count);
+        xa.list_stride = P;
+        xa.list_tokens = P;
+        if ((e = launch_gateup_mfma(xa, act, sq_all, hq, c->compute)) != hipSuccess)
           return c->hip_fail(e, "gate/up MFMA kernel");
         if ((e = launch_down_mfma(xa, act, hq, c->compute)) != hipSuccess) return c->hip_fail(e, "down MFMA kernel");
       } else {
         if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
         if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
       }
-      if (cfg.accumulate_defaults &&
-          (e = launch_accumulate_defaults(xa, act, c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H,
-                                          c->at<unsigned long long>(c->lay.dacc_cnt) + size_t(layer) * E,
-                                          c->compute)) != hipSuccess)
-        return c->hip_fail(e, "default-vector accumulation");
+      if (cfg.accumulate_defaults)
+        for (int u0 = t0; u0 < (all_at_once ? P : t0 + nb); u0 += MB) {
+          ExpertArgs ya = xa;                          // per micro-batch: the kernel indexes positions from 0
+          ya.exec_ids = ids_all + size_t(u0) * k;
+          ya.y = y_all + size_t(u0) * k * H;
+          ya.B = std::min(MB, P - u0);
+          if ((e = launch_accumulate_defaults(ya, act, c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H,
+                                              c->at<unsigned long long>(c->lay.dacc_cnt) + size_t(layer) * E,
+                                              c->compute)) != hipSuccess)
+            return c->hip_fail(e, "default-vector accumulation");
+        }
       c->st.hbm_bytes_algorithmic += int64_t(n_here) * int64_t(c->expert_bytes);
     }
     c->close_span(sp_exec, c->compute);
@@ -1015,7 +1036,7 @@ int moe_spec_reset(moe_spec_ctx *c) {
   if ((e = hipMemsetAsync(c->arena + c->lay.diag, 0, size_t(c->cfg.n_layers) * sizeof(LayerDiag), c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear counters");
   if (c->cfg.accumulate_defaults &&
-      (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.total - c->lay.dacc_sum, c->compute)) != hipSuccess)
+      (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.pf_s - c->lay.dacc_sum, c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear sums");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
   c->st = moe_spec_stats_t{};

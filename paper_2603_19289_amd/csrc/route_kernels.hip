@@ -2,7 +2,9 @@
 // layer and for the prediction of the next layer's routing from the quasi-hidden state
 // (paper: Sec. 3.1-3.3; Algorithm 1, TopK(Gate_l(X)) and GetNextExperts).
 //
-// One launch covers the whole batch.  Every workgroup normalises the input rows itself (they
+// One launch covers the whole batch; the batch is cut into groups of tok_tile tokens (grid
+// dimension y), each with its own arrival counter, so that large batches fill the chip while a
+// batch of one keeps the single short dependency chain.  Every workgroup normalises the input rows of its group itself (they
 // are a few KB and sit in L2), keeps them in LDS in double precision, and one wavefront per
 // router row streams that row once with 16-byte loads.  Logits go to global memory; the last
 // workgroup to arrive (a ticket counter, no waiting) rank-sorts them in registers (keys stay in
@@ -56,11 +58,11 @@ struct FinishShared {
 
 // Top-k, gates and bookkeeping of all tokens by the whole (last) workgroup, one token at a time.
 template <int R>
-__device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
+__device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid, int b_begin, int b_end) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int kSrcPerWave = kWave / (kRouteBlock / kWave);
   if (tid == 0) sh.hits = 0;
-  for (int b = 0; b < a.B; ++b) {
+  for (int b = b_begin; b < b_end; ++b) {
     double key[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -112,7 +114,7 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid) {
   }
   if (tid == 0 && a.cmp_ids) {
     atomicAdd(&a.diag->hits, static_cast<unsigned long long>(sh.hits));
-    atomicAdd(&a.diag->preds, static_cast<unsigned long long>(a.k) * a.B);
+    atomicAdd(&a.diag->preds, static_cast<unsigned long long>(a.k) * (b_end - b_begin));
   }
 }
 
@@ -145,8 +147,9 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
     }
   }
 
-  for (int b0 = 0; b0 < a.B; b0 += a.tok_tile) {
-    const int nb = min(a.tok_tile, a.B - b0);
+  const int b_begin = blockIdx.y * a.tok_tile, b_end = min(a.B, b_begin + a.tok_tile);   // this group's tokens
+  for (int b0 = b_begin; b0 < b_end; b0 += a.tok_tile) {
+    const int nb = min(a.tok_tile, b_end - b0);
     for (int t = 0; t < nb; ++t) {
       const int b = b0 + t;
       double *v = vec + size_t(t) * H;
@@ -318,25 +321,33 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
     __syncthreads();                         // vec is rewritten by the next tile
   }
 
-  // Hand the logits to whichever workgroup arrives last.
+  // Hand the group's logits to whichever of its workgroups arrives last.
+  unsigned int *arrivals = a.counter + 1 + blockIdx.y;
   __threadfence();
   __syncthreads();
   if (tid == 0) {
-    const unsigned int ticket = atomicAdd(a.counter, 1u);
+    const unsigned int ticket = atomicAdd(arrivals, 1u);
     last_flag = (ticket == gridDim.x - 1);
   }
   __syncthreads();
   if (!last_flag) return;
   __threadfence();
 
-  if (a.E <= kWave) finish_tokens<1>(a, fin, tid);
-  else if (a.E <= 2 * kWave) finish_tokens<2>(a, fin, tid);
-  else finish_tokens<4>(a, fin, tid);
+  if (a.E <= kWave) finish_tokens<1>(a, fin, tid, b_begin, b_end);
+  else if (a.E <= 2 * kWave) finish_tokens<2>(a, fin, tid, b_begin, b_end);
+  else finish_tokens<4>(a, fin, tid, b_begin, b_end);
   if (a.mailbox) __threadfence_system();
   __syncthreads();
   if (tid == 0) {
-    *a.counter = 0u;
-    if (a.mailbox)
+    *arrivals = 0u;
+    // the ids are complete when every group is: the last group to finish tells the host
+    bool all_done = true;
+    if (gridDim.y > 1) {
+      __threadfence();
+      all_done = atomicAdd(a.counter, 1u) == gridDim.y - 1;
+      if (all_done) { __threadfence(); *a.counter = 0u; }
+    }
+    if (all_done && a.mailbox)
       __hip_atomic_store(&a.mailbox->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
@@ -361,7 +372,8 @@ hipError_t launch_route_n(const RouteArgs &args, size_t lds, hipStream_t st) {
     if (e != hipSuccess) return e;
     big_lds_allowed = true;
   }
-  const dim3 grid((args.E + kRouteRowsPerBlock - 1) / kRouteRowsPerBlock), block(kRouteBlock);
+  const dim3 grid((args.E + kRouteRowsPerBlock - 1) / kRouteRowsPerBlock,
+                  (args.B + args.tok_tile - 1) / args.tok_tile), block(kRouteBlock);
   hipLaunchKernelGGL((route_kernel<WT, NCH>), grid, block, lds, st, args);
   return hipGetLastError();
 }

@@ -28,11 +28,14 @@ def prompt_of(wl, P):
     return x0[0], eps[0]
 
 
-def run_prefill(wl, P, max_batch, label, **engine_kw):
+def run_prefill(wl, P, max_batch, label, prebuilt=None, **engine_kw):
     from paper_2603_19289_amd.engine import engine_for
     print(f"[case] prefill {label} L={wl.n_layers} H={wl.hidden} E={wl.n_experts} k={wl.top_k} I={wl.inter} "
           f"P={P} micro-batch={max_batch} S={wl.slots} {wl.dtype} {engine_kw}", flush=True)
-    res, ex, model = build(wl, "random")
+    if prebuilt is None:
+        res, ex, model = build(wl, "random")
+    else:
+        res, model, ex = prebuilt
     r_np, eps = prompt_of(wl, P)
     orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
     eng = engine_for(wl, O.MODE_SPECULATIVE, res, ex, max_batch=max_batch, max_prefill_tokens=P + 3, **engine_kw)
@@ -83,6 +86,46 @@ def test_prefill_single_slot_and_single_token():
 def test_prefill_pool_larger_than_expert_count():
     wl = small_workload(n_layers=1, dtype="bf16", slots=40)         # both halves hold all 8 experts: one group
     run_prefill(wl, P=21, max_batch=16, label="S>2E", copy_engine=M.COPY_KERNEL)
+
+
+@pytest.mark.parametrize("name,P,layers", [("c2_qwen3_30b_a3b", 150, 2), ("c3_gpt_oss_20b", 70, 1)])
+def test_prefill_at_full_layer_shape(name, P, layers):
+    """The benchmark's layer shape and slot count, micro-batches of 64 tokens plus a ragged tail."""
+    from tests.test_gpu_full_shapes import prebuilt
+    wl = W.CONFIGS[name].with_(n_layers=layers, tokens=1)
+    run_prefill(wl, P=P, max_batch=64, label=name, prebuilt=prebuilt(wl), copy_engine=M.COPY_DMA2)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_default_vectors_calibrated_by_prefill(dtype):
+    """Offline calibration (Sec. 3.1): two prompts through the prefill step with accumulation on; the
+    per-expert mean outputs and execution counts equal the checker's."""
+    from paper_2603_19289_amd.engine import engine_for
+    wl = small_workload(n_layers=2, hidden=136, n_experts=12, top_k=3, inter=104, dtype=dtype, slots=6, seed=23)
+    res, ex, model = build(wl, "random")
+    orc = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots)
+    eng = engine_for(wl, O.MODE_ON_DEMAND, res, ex, max_batch=16, max_prefill_tokens=64, accumulate_defaults=1,
+                     copy_engine=M.COPY_DMA)
+    try:
+        for P, seed in ((41, 23), (18, 24)):
+            r_np, eps = prompt_of(dataclasses.replace(wl, seed=seed), P)
+            for l in range(wl.n_layers):
+                want = orc.prefill_layer_step(l, r_np)
+                out, _, _ = eng.prefill_layer_step(l, torch.from_numpy(r_np.astype(np.float32)).to("cuda"))
+                torch.cuda.synchronize()
+                assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL[dtype]
+                r_np = W.advance_residual(wl, r_np, want.out, eps[l])
+        for l in range(wl.n_layers):
+            mean, counts = eng.read_default_vectors(l)
+            assert counts == orc.dacc_cnt[l].tolist()
+            got, want = mean.cpu().numpy().astype(np.float64), orc.default_vectors(l)
+            for e in range(wl.n_experts):
+                if counts[e]:
+                    assert np.linalg.norm(got[e] - want[e]) <= TOL[dtype] * np.linalg.norm(want[e]), (l, e)
+                else:
+                    assert not got[e].any()
+    finally:
+        eng.close()
 
 
 @pytest.mark.parametrize("mode", [O.MODE_SPECULATIVE, O.MODE_ON_DEMAND])
