@@ -84,7 +84,7 @@ typedef struct {
                                        un-gated outputs of every executed expert (the offline statistic
                                        behind the default vectors, Sec. 3.1); costs L*E*H doubles of arena
                                        and disables the fused batch-1 down+combine kernel */
-  int32_t max_prefill_tokens;       /* P_max >= 0: most prompt tokens one moe_spec_prefill_layer_step takes;
+  int32_t max_prefill_tokens;       /* 0 <= P_max <= 32768: most prompt tokens one moe_spec_prefill_layer_step takes;
                                        0: no prefill path.  Costs about P_max*(k+2)*H floats of arena */
   int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
                                        feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
@@ -172,7 +172,10 @@ int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int bat
  * streamed from the host pool through the layer's slots, half of the slots receiving the next group
  * of experts while the kernels run on the other half, and every token executes its true top-k
  * experts.  Copies depend on no routing result, so the copy stream runs ahead of the compute stream
- * into the following layers' calls (the layer-ahead loading of the paper); the call never blocks.
+ * into the following layers' calls (the layer-ahead loading of the paper).  The call returns when
+ * all of the layer's copies and kernels are queued; with more than S experts it waits on the host
+ * for the kernels of the group before last, so it returns about one group of copies before the
+ * layer's last transfer ends.
  * r_dev [n_tokens,H] float, out_dev [n_tokens,H] float (valid in compute-stream order),
  * 1 <= n_tokens <= max_prefill_tokens (MOE_SPEC_EINVAL otherwise).  true_ids / true_gates: dev
  * [n_tokens,k] or NULL.  Any layer order; not between begin_token and a token's last layer_step

@@ -65,7 +65,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->predict_signal != 0 && c->predict_signal != 1) return "unknown predict_signal";
   if (c->est_latent < 0 || c->est_ffn < 0 || (c->est_latent == 0) != (c->est_ffn == 0)) return "estimator sizes must both be set or both be 0";
   if (c->est_latent % 8 || c->est_ffn % 8) return "estimator sizes must be multiples of 8";
-  if (c->max_prefill_tokens < 0 || c->max_prefill_tokens > 65536) return "max_prefill_tokens out of range";
+  if (c->max_prefill_tokens < 0 || c->max_prefill_tokens > 32768) return "max_prefill_tokens out of range";
   if (c->est_latent > MOE_SPEC_MAX_HIDDEN || c->est_ffn > 8 * MOE_SPEC_MAX_HIDDEN) return "estimator sizes too large";
   return nullptr;
 }
@@ -876,7 +876,15 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
   // --- stream every expert through the two halves of the pool
   for (int e0 = 0, g = 0; e0 < E; e0 += group, ++g) {
     const int half = g % halves, n_here = std::min(group, E - e0);
-    if (g >= halves) { int rc = c->copy_queues_wait(c->pf_done[half]); if (rc) return rc; }
+    if (g >= halves) {
+      // The slots were last read by the kernels of group g - halves.  The host waits for them here
+      // (the copy engines are then still busy with group g - 1, so they never run dry): a copy
+      // queued behind an event that has already completed starts without a cross-queue barrier,
+      // and such barriers cost the DMA queues about 0.1 ms each.
+      if ((e = hipEventSynchronize(c->pf_done[half])) != hipSuccess) return c->hip_fail(e, "wait for the kernels of an earlier group");
+      int rc = c->copy_queues_wait(c->pf_done[half]);
+      if (rc) return rc;
+    }
     TimedSpan *sp_copy = c->open_span(1, c->copy);
     CopyList cl{};
     cl.n16 = uint32_t(c->expert_bytes / 16);
@@ -947,12 +955,12 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
 
   // --- gate-weighted sums
   TimedSpan *sp_comb = c->open_span(0, c->compute);
-  for (int t0 = 0; t0 < P; t0 += MB) {
-    ExpertArgs xa{};
-    xa.exec_gates = gates_all + size_t(t0) * k;
-    xa.y = y_all + size_t(t0) * k * H;
-    xa.out = out + size_t(t0) * H;
-    xa.B = std::min(MB, P - t0); xa.k = k; xa.H = H; xa.I = I;
+  {
+    ExpertArgs xa{};                                   // one launch: a grid row per token
+    xa.exec_gates = gates_all;
+    xa.y = y_all;
+    xa.out = out;
+    xa.B = P; xa.k = k; xa.H = H; xa.I = I;
     if ((e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
   }
   c->close_span(sp_comb, c->compute);
