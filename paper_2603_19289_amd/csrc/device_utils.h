@@ -37,6 +37,17 @@ __device__ __forceinline__ void load_chunk(const WT *p, float (&f)[Packed<WT>::N
   Packed<WT>::unpack(*reinterpret_cast<const typename Packed<WT>::Raw *>(p), f);
 }
 
+// 16-byte load of data that is read once (expert weights streamed from the slots): the
+// nontemporal hint keeps such lines from displacing what the caches should hold and measurably
+// raises the streaming rate (pure read of 50 MB: 5.0 -> 5.2 TB/s; of 470 MB: 6.3 -> 7.0 TB/s).
+typedef __attribute__((ext_vector_type(4))) unsigned int vec4u_t;
+template <typename RAW>
+__device__ __forceinline__ RAW load_stream(const void *p) {
+  static_assert(sizeof(RAW) == 16, "16-byte chunks only");
+  const vec4u_t v = __builtin_nontemporal_load(reinterpret_cast<const vec4u_t *>(p));
+  return __builtin_bit_cast(RAW, v);
+}
+
 // Dot product of one packed weight chunk with one packed activation chunk of the same dtype,
 // added to acc in float.  bf16: four two-element dot instructions per 16 bytes (both operands
 // stay packed; every product is exact in float).  float: four multiply-adds.

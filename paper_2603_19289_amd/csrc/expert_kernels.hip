@@ -190,8 +190,8 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
   typename R::Raw rg[NCH], ru[NCH];
 #pragma unroll
   for (int ch = 0; ch < NCH; ++ch) {
-    rg[ch] = *reinterpret_cast<const typename R::Raw *>(wg + size_t(row0) * H + col[ch]);
-    ru[ch] = *reinterpret_cast<const typename R::Raw *>(wu + size_t(row0) * H + col[ch]);
+    rg[ch] = load_stream<typename R::Raw>(wg + size_t(row0) * H + col[ch]);
+    ru[ch] = load_stream<typename R::Raw>(wu + size_t(row0) * H + col[ch]);
   }
   float sv[NCH][VN];
 #pragma unroll
@@ -216,8 +216,8 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
     if (row + 1 < row_end) {
 #pragma unroll
       for (int ch = 0; ch < NCH; ++ch) {
-        rg[ch] = *reinterpret_cast<const typename R::Raw *>(wg + size_t(row + 1) * H + col[ch]);
-        ru[ch] = *reinterpret_cast<const typename R::Raw *>(wu + size_t(row + 1) * H + col[ch]);
+        rg[ch] = load_stream<typename R::Raw>(wg + size_t(row + 1) * H + col[ch]);
+        ru[ch] = load_stream<typename R::Raw>(wu + size_t(row + 1) * H + col[ch]);
       }
     }
     const float g = wave_sum(ag);
@@ -230,39 +230,120 @@ __global__ __launch_bounds__(kBlock) void gateup_b1_kernel(const ExpertArgs a, c
   }
 }
 
+// Small launches (all wavefronts resident at once): a wavefront owns two consecutive rows and
+// issues the 4*NCH 16-byte loads of both before it reduces anything.
+template <typename WT, int NCH>
+__global__ __launch_bounds__(kBlock) void gateup_b1_pair_kernel(const ExpertArgs a, const ActiveList act) {
+  using R = Packed<WT>;
+  constexpr int VN = R::N;
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
+  const int H = a.H, I = a.I;
+  const int row0 = (blockIdx.x * kWaves + wave) * 2;
+  if (row0 >= I) return;
+  const int pos = blockIdx.y;
+  const WT *wg = reinterpret_cast<const WT *>(a.pool + size_t(act.slot[pos]) * a.slot_bytes);
+  const WT *wu = wg + size_t(I) * H;
+  WT *hq = reinterpret_cast<WT *>(a.h) + size_t(pos) * I;
+
+  int col[NCH];
+  bool live[NCH];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+    col[ch] = (ch * kWave + lane) * VN;
+    live[ch] = col[ch] < H;
+    if (!live[ch]) col[ch] = 0;                // dead lanes re-read column 0 and multiply by zero
+  }
+  typename R::Raw rg[2][NCH], ru[2][NCH];
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int row = min(row0 + r, I - 1);      // an odd last row is loaded twice and stored once
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      rg[r][ch] = load_stream<typename R::Raw>(wg + size_t(row) * H + col[ch]);
+      ru[r][ch] = load_stream<typename R::Raw>(wu + size_t(row) * H + col[ch]);
+    }
+  }
+  float sv[NCH][VN];
+#pragma unroll
+  for (int ch = 0; ch < NCH; ++ch) {
+#pragma unroll
+    for (int x = 0; x < VN; x += 4) {
+      const float4 f = *reinterpret_cast<const float4 *>(a.s + col[ch] + x);
+      const float m = live[ch] ? 1.f : 0.f;
+      sv[ch][x] = f.x * m; sv[ch][x + 1] = f.y * m; sv[ch][x + 2] = f.z * m; sv[ch][x + 3] = f.w * m;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    if (row0 + r >= I) break;
+    float ag = 0.f, au = 0.f;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+      float fg[VN], fu[VN];
+      R::unpack(rg[r][ch], fg);
+      R::unpack(ru[r][ch], fu);
+#pragma unroll
+      for (int x = 0; x < VN; ++x) { ag += fg[x] * sv[ch][x]; au += fu[x] * sv[ch][x]; }
+    }
+    const float g = wave_sum(ag);
+    const float u = wave_sum(au);
+    if (lane == 0) {
+      float hv = g / (1.f + expf(-g)) * u;
+      if (a.bf16) hv = round_to_bf16(hv);
+      hq[row0 + r] = R::pack_one(hv);
+    }
+  }
+}
+
 // O[row] = sum_j gate_j * (W_down_{e_j}[row,:] . hq[j,:]) for the one token of the batch: the down
-// projection of all k executed experts and the gate-weighted combine in one pass, no LDS and no
-// barrier.  One wavefront owns one output row.  The k rows it needs (one per expert, I values
-// each) are walked as one flat list of 16-byte chunks so that all 64 lanes load on every
-// iteration whatever I is; each lane folds the gate of its chunk's expert into its partial
-// sum, and a single reduction per row remains.  `act` is in execution-position order.
-template <typename WT>
+// projection of all k executed experts and the gate-weighted combine in one pass.  SPLIT
+// wavefronts share one output row.  The k rows it needs (one per expert, I values each) are
+// walked as one flat list of 16-byte chunks so that all 64 lanes load on every iteration
+// whatever I is; each lane folds the gate of its chunk's expert into its partial sum, one
+// reduction per wavefront remains, and the SPLIT partial sums meet in LDS.  `act` is in
+// execution-position order.
+template <typename WT, int SPLIT, int UNROLL>
 __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArgs a, const ActiveList act,
                                                                  const float inv_chunks) {
   using R = Packed<WT>;
   constexpr int VN = R::N;
+  __shared__ float part_sum[kWaves];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int H = a.H, I = a.I, k = a.k;
-  const int row = blockIdx.x * kWaves + wave;
-  if (row >= H) return;
+  const int row = blockIdx.x * (kWaves / SPLIT) + wave / SPLIT;
+  const int part = wave % SPLIT;
+  const bool valid = row < H;
   const int chunks = I / VN;                   // per expert row
   const int total = chunks * k;
   const WT *hq = reinterpret_cast<const WT *>(a.h);
-  const size_t down_off = (size_t(2) * I * H + size_t(row) * I) * sizeof(WT);
+  const size_t down_off = (size_t(2) * I * H + size_t(valid ? row : 0) * I) * sizeof(WT);
   float acc = 0.f;
-#pragma unroll 4
-  for (int t = lane; t < total; t += kWave) {
-    int j = int(float(t) * inv_chunks);        // t / chunks, fixed up below (t < 2^24 is exact in float)
-    j -= (j * chunks > t);
-    j += ((j + 1) * chunks <= t);
-    const int c = (t - j * chunks) * VN;
-    const char *base = a.pool + size_t(act.slot[j]) * a.slot_bytes + down_off;
-    const typename R::Raw w = *reinterpret_cast<const typename R::Raw *>(base + size_t(c) * sizeof(WT));
-    const typename R::Raw hh = *reinterpret_cast<const typename R::Raw *>(hq + size_t(j) * I + c);
-    acc += a.exec_gates[j] * dot_chunk(w, hh, 0.f);
+  if (valid) {
+#pragma unroll UNROLL
+    for (int t = part * kWave + lane; t < total; t += kWave * SPLIT) {
+      int j = int(float(t) * inv_chunks);      // t / chunks, fixed up below (t < 2^24 is exact in float)
+      j -= (j * chunks > t);
+      j += ((j + 1) * chunks <= t);
+      const int c = (t - j * chunks) * VN;
+      const char *base = a.pool + size_t(act.slot[j]) * a.slot_bytes + down_off;
+      const typename R::Raw w = load_stream<typename R::Raw>(base + size_t(c) * sizeof(WT));
+      const typename R::Raw hh = *reinterpret_cast<const typename R::Raw *>(hq + size_t(j) * I + c);
+      acc += a.exec_gates[j] * dot_chunk(w, hh, 0.f);
+    }
   }
   const float v = wave_sum(acc);
-  if (lane == 0) a.out[row] = v;
+  if (SPLIT == 1) {
+    if (lane == 0 && valid) a.out[row] = v;
+  } else {
+    if (lane == 0) part_sum[wave] = v;
+    __syncthreads();
+    if (lane == 0 && part == 0 && valid) {
+      float tot = 0.f;
+#pragma unroll
+      for (int p = 0; p < SPLIT; ++p) tot += part_sum[wave + p];
+      a.out[row] = tot;
+    }
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -462,7 +543,7 @@ __global__ __launch_bounds__(kBlock) void stream_read_kernel(const ExpertArgs a,
   const size_t stride = size_t(gridDim.x) * kBlock;
   float acc = 0.f;
   for (size_t i = size_t(blockIdx.x) * kBlock + threadIdx.x; i < n16; i += stride) {
-    const uint4 v = p[i];
+    const uint4 v = load_stream<uint4>(p + i);
     acc += __uint_as_float(v.x ^ v.y ^ v.z ^ v.w);
   }
   if (acc == 1.2345e-30f) *sink = acc;
@@ -549,10 +630,17 @@ hipError_t launch_down_t(const ExpertArgs &a, const ActiveList &act, hipStream_t
 
 template <typename WT, int NCH>
 void launch_gateup_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  const dim3 block(kBlock);
+  // up to 4096 wavefronts of two rows each are all resident at once (137 registers at NCH = 4)
+  if (NCH <= 4 && long(a.I) * act.n <= 8192) {
+    const dim3 grid((a.I + 2 * kWaves - 1) / (2 * kWaves), act.n);
+    hipLaunchKernelGGL((gateup_b1_pair_kernel<WT, NCH>), grid, block, 0, st, a, act);
+    return;
+  }
   // one row per wavefront until that would exceed about 6144 wavefronts (24 per compute unit)
   long rpw = (long(a.I) * act.n + 6143) / 6144;
   if (rpw < 1) rpw = 1;
-  const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n), block(kBlock);
+  const dim3 grid((a.I + kWaves * rpw - 1) / (kWaves * rpw), act.n);
   hipLaunchKernelGGL((gateup_b1_kernel<WT, NCH>), grid, block, 0, st, a, act, int(rpw));
 }
 
@@ -571,11 +659,27 @@ bool launch_gateup_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st
   return true;
 }
 
+template <typename WT, int SPLIT, int UNROLL>
+void launch_down_combine_b1_n(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
+  const dim3 grid((a.H + kWaves / SPLIT - 1) / (kWaves / SPLIT)), block(kBlock);
+  const float inv_chunks = 1.0f / float(a.I / Packed<WT>::N);
+  hipLaunchKernelGGL((down_combine_b1_kernel<WT, SPLIT, UNROLL>), grid, block, 0, st, a, act, inv_chunks);
+}
+
+// The loop of a wavefront is unrolled UNROLL times, so that many loads per lane are in flight
+// together; where a row's chunk list is short enough, SPLIT is chosen so that each wavefront's
+// share is exactly one such batch (iterations beyond a multiple of UNROLL run one by one).
+// Otherwise four wavefronts per row and batches of four, the best measured on the 1440- and
+// 3584-chunk rows of the larger workloads.
 template <typename WT>
 void launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
-  const dim3 grid((a.H + kWaves - 1) / kWaves), block(kBlock);
-  const float inv_chunks = 1.0f / float(a.I / Packed<WT>::N);
-  hipLaunchKernelGGL((down_combine_b1_kernel<WT>), grid, block, 0, st, a, act, inv_chunks);
+  const long chunks = long(a.I / Packed<WT>::N) * a.k;
+  const long iters = chunks % kWave == 0 ? chunks / kWave : 0;      // per row, for one wavefront
+  if (iters == 4) launch_down_combine_b1_n<WT, 1, 4>(a, act, st);
+  else if (iters == 6) launch_down_combine_b1_n<WT, 1, 6>(a, act, st);
+  else if (iters == 8) launch_down_combine_b1_n<WT, 2, 4>(a, act, st);
+  else if (iters == 12) launch_down_combine_b1_n<WT, 2, 6>(a, act, st);
+  else launch_down_combine_b1_n<WT, 4, 4>(a, act, st);
 }
 
 template <bool GATEUP>

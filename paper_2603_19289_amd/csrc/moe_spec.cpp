@@ -445,7 +445,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   if ((e = hipMemsetAsync(c->arena + lay.counter, 0, (1 + kMaxBatch) * sizeof(unsigned int), c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
   if (cfg->accumulate_defaults) {
-    if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.total - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
+    if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.pf_s - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
   }
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return bail(e, "synchronize");
   *out = c;
