@@ -128,6 +128,23 @@ def test_wide_hidden_sizes_take_the_streaming_fallbacks(dtype, H):
     run_teacher_forced(wl, O.MODE_SPECULATIVE)
 
 
+@pytest.mark.parametrize("dtype,H,I,k,what", [
+    ("bf16", 256, 768, 4, "down: 384 chunks per row, one wavefront, six loads per lane"),
+    ("bf16", 256, 1024, 4, "down: 512 chunks, two wavefronts of four loads"),
+    ("bf16", 256, 776, 4, "down: a chunk count that is no multiple of 64, four wavefronts with a ragged end"),
+    ("f32", 128, 520, 3, "down: float32 rows with a ragged end; gate/up: pair kernel with few rows"),
+    ("bf16", 512, 2048, 4, "gate/up: 8192 rows, the largest launch of the two-rows-per-wavefront kernel"),
+    ("bf16", 512, 2056, 4, "gate/up: 8224 rows, the smallest launch of the pipelined kernel"),
+    ("bf16", 2560, 72, 2, "gate/up: five register chunks per lane, pipelined kernel whatever the row count"),
+])
+def test_batch_one_kernel_variants(dtype, H, I, k, what):
+    # the launchers of the batch-1 expert kernels pick a kernel and its shape from I, k and H
+    wl = small_workload(name="b1_variant", n_layers=2, hidden=H, n_experts=6, top_k=k, inter=I, dtype=dtype,
+                        batch=1, tokens=2, slots=k + 1, seed=83)
+    run_teacher_forced(wl, O.MODE_SPECULATIVE, label=what)
+    run_teacher_forced(wl, O.MODE_ON_DEMAND, label=what)
+
+
 @pytest.mark.parametrize("mode", list(MODES))
 def test_caption_reading_of_the_quasi_hidden_state(mode):
     run_teacher_forced(small_workload(name="caption", n_layers=4, tokens=4), MODES[mode], q_from_normalized=1)
