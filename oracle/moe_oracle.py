@@ -502,6 +502,22 @@ class MoEOracle:
                           t_margin, n_margin, s, q_all)
 
 
+def tpot_model(t_compute, t_copy):
+    """Analytic decode-time model of Sec. 5.1: per-layer compute times (attention + routing + expert
+    FFN) and per-layer expert-copy times give
+        T_ond = sum_l (t_compute_l + t_copy_l)          on-demand loading, copies on the critical path
+        T_pf  = sum_l max(t_compute_l, t_copy_l)        prefetching, copy overlapped with compute
+        dT    = sum_l min(t_copy_l, t_compute_l)        the equation labelled "improvement"
+    under the paper's assumption that consecutive layers copy the same amount (the copy that
+    overlaps layer l's compute is the one for layer l+1).  Returns (T_ond, T_pf, dT)."""
+    t_compute = np.asarray(t_compute, dtype=np.float64)
+    t_copy = np.asarray(t_copy, dtype=np.float64)
+    t_ond = float(np.sum(t_compute + t_copy))
+    t_pf = float(np.sum(np.maximum(t_compute, t_copy)))
+    delta = float(np.sum(np.minimum(t_copy, t_compute)))
+    return t_ond, t_pf, delta
+
+
 def run_tokens(oracle: MoEOracle, x0, advance, n_layers: Optional[int] = None):
     """Drive the oracle over decode steps.  x0 is [T, B, H]; `advance(t, l, r, O)` is the
     caller's residual update (the stand-in for everything between two MoE blocks) and

@@ -269,3 +269,41 @@ def test_estimator_special_cases():
     u = est.proj.astype(np.float64) @ q + est.layer_emb[1]
     want = (u - u.mean()) / np.sqrt(u.var() + est.ln_eps)
     np.testing.assert_allclose(O.estimator_logits(est, q, 1), want, rtol=1e-12)
+
+
+# --------------------------------------------------------------------------------------
+# Analytic decode-time model (Sec. 5.1)
+# --------------------------------------------------------------------------------------
+def _golden_tpot_cases():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "tpot_model.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, comp, copy, t_ond, t_pf, delta = [f.strip() for f in line.split("|")]
+        yield (name, [float(x) for x in comp.split()], [float(x) for x in copy.split()],
+               float(t_ond), float(t_pf), float(delta))
+
+
+def test_tpot_model_matches_the_stated_cases():
+    cases = list(_golden_tpot_cases())
+    assert len(cases) >= 4
+    for name, comp, copy, t_ond, t_pf, delta in cases:
+        got = O.tpot_model(comp, copy)
+        np.testing.assert_allclose(got, (t_ond, t_pf, delta), rtol=1e-12, err_msg=name)
+
+
+def test_tpot_model_invariants():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        L = int(rng.integers(1, 40))
+        comp, copy = rng.random(L) * 3, rng.random(L) * 3
+        t_ond, t_pf, delta = O.tpot_model(comp, copy)
+        assert abs((t_ond - t_pf) - delta) < 1e-9            # what prefetching saves is the improvement
+        assert delta <= min(comp.sum(), copy.sum()) + 1e-12   # bounded by total compute and by total copy
+        assert t_ond / t_pf <= 2.0 + 1e-12                    # the 2x ceiling of Sec. 5.1
+        # brute force, layer by layer
+        assert abs(t_pf - sum(max(a, b) for a, b in zip(comp, copy))) < 1e-9
+    t_ond, t_pf, _ = O.tpot_model([2.0] * 7, [2.0] * 7)
+    assert t_ond / t_pf == 2.0
