@@ -20,6 +20,19 @@ namespace {
 
 constexpr int kMaxTokTile = 4;
 
+// Logits travel from the workgroups that compute them to the one that sorts them through
+// device-scope atomic stores and loads, which bypass the per-XCD L2 caches' non-coherent lines.
+// The writers wait until those stores are acknowledged before they take their ticket, so no
+// device-scope fence is needed on this path: such a fence writes back and invalidates the whole
+// L2 of the XCD, and a launch of a thousand workgroups spent more time in those than in its
+// arithmetic (B = 32: 55 us with fences).
+__device__ __forceinline__ void store_coherent(double *p, double v) {
+  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p),
+                     static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void wait_for_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 __device__ __forceinline__ double load_coherent(const double *p) {
   const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -314,7 +327,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
       for (int t = 0; t < kMaxTokTile; ++t) {
         if (t < nb) {
           const double s = wave_sum(acc[t]);
-          if (lane == 0) a.z[size_t(b0 + t) * a.E + row] = s;
+          if (lane == 0) store_coherent(a.z + size_t(b0 + t) * a.E + row, s);
         }
       }
     }
@@ -323,15 +336,15 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
 
   // Hand the group's logits to whichever of its workgroups arrives last.
   unsigned int *arrivals = a.counter + 1 + blockIdx.y;
-  __threadfence();
+  wait_for_stores();                           // this wavefront's logits have reached memory
   __syncthreads();
   if (tid == 0) {
-    const unsigned int ticket = atomicAdd(arrivals, 1u);
+    const unsigned int ticket = __hip_atomic_fetch_add(arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     last_flag = (ticket == gridDim.x - 1);
   }
   __syncthreads();
   if (!last_flag) return;
-  __threadfence();
+  asm volatile("" ::: "memory");               // the logit loads below stay below
 
   if (a.E <= kWave) finish_tokens<1>(a, fin, tid, b_begin, b_end);
   else if (a.E <= 2 * kWave) finish_tokens<2>(a, fin, tid, b_begin, b_end);
@@ -354,13 +367,14 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
 
 }  // namespace
 
+// One token per group: the per-token chain (load, reduce, normalise, row products, ticket, sort)
+// is a sequence of dependent latencies, so tokens side by side in separate workgroups finish in
+// the time of one, while tokens one after the other in one workgroup add about 10 us each.  The
+// router rows are then read once per token, from L2 after the first.
 size_t route_lds_bytes(int H, int B, int *tok_tile) {
-  int tt = int((size_t(48) << 10) / (size_t(H) * sizeof(double)));
-  if (tt < 1) tt = 1;
-  if (tt > kMaxTokTile) tt = kMaxTokTile;
-  if (tt > B) tt = B;
-  *tok_tile = tt;
-  return size_t(tt) * H * sizeof(double);
+  (void)B;
+  *tok_tile = 1;
+  return size_t(H) * sizeof(double);
 }
 
 template <typename WT, int NCH>
