@@ -2,15 +2,15 @@
 // layer and for the prediction of the next layer's routing from the quasi-hidden state
 // (paper: Sec. 3.1-3.3; Algorithm 1, TopK(Gate_l(X)) and GetNextExperts).
 //
-// One launch covers the whole batch; the batch is cut into groups of tok_tile tokens (grid
-// dimension y), each with its own arrival counter, so that large batches fill the chip while a
-// batch of one keeps the single short dependency chain.  Every workgroup normalises the input rows of its group itself (they
-// are a few KB and sit in L2), keeps them in LDS in double precision, and one wavefront per
-// router row streams that row once with 16-byte loads.  Logits go to global memory; the last
-// workgroup to arrive (a ticket counter, no waiting) rank-sorts them in registers (keys stay in
-// VGPRs, broadcast lane by lane through scalar registers), writes ids and gates, scores the
-// previous prediction, and posts the ids to a pinned
-// host mailbox.  Everything that decides an expert index is double precision.
+// One launch covers the whole batch: grid dimension y is the token, each token with its own
+// arrival counter, so tokens run side by side and a batch costs little more than its slowest
+// token.  Every workgroup of a token normalises the token's input row itself (a few KB from L2),
+// keeps it in LDS in double precision, and one wavefront per router row reads that row once
+// with 16-byte loads.  Logits go to global memory; the last of the token's workgroups to arrive
+// (a ticket counter, no waiting) rank-sorts them in registers (keys stay in VGPRs, broadcast lane
+// by lane through scalar registers), writes ids and gates and scores the previous prediction;
+// the last token to finish posts the ids to a pinned host mailbox.  Everything that decides an
+// expert index is double precision.
 // Layer order of the default-vector sum follows the id order (descending logit).
 #include "device_utils.h"
 #include "kernels.h"
@@ -18,7 +18,7 @@
 namespace moe_spec {
 namespace {
 
-constexpr int kMaxTokTile = 4;
+constexpr int kMaxTokTile = 1;     // tokens a workgroup handles (one: see route_lds_bytes)
 
 // Logits travel from the workgroups that compute them to the one that sorts them through
 // device-scope atomic stores and loads, which bypass the per-XCD L2 caches' non-coherent lines.
