@@ -45,8 +45,8 @@ def parse():
                         "state and for the baseline signal s_l (the statistics of the paper's per-layer figures)")
     p.add_argument("--calibrate-copy", action="store_true",
                    help="also run one plain 256 MiB device-to-device copy (reference dispatch for scaling PMC byte counters)")
-    p.add_argument("--prefill", type=int, default=0, metavar="P",
-                   help="also time the prefill step on a prompt of P tokens (every expert of every layer streamed)")
+    p.add_argument("--prefill", type=int, default=512, metavar="P",
+                   help="also time the prefill step on a prompt of P tokens (every expert of every layer streamed); 0 = skip")
     p.add_argument("--kernel-reps", type=int, default=480)
     p.add_argument("--copy-engine", choices=["auto", "kernel", "dma", "dma2"], default="auto",
                    help="auto: each mode gets the engine that is fastest for it (speculative: four DMA queues, "
