@@ -187,19 +187,24 @@ def main():
     #      mean launch duration inside the two instrumented token loops (event pairs on the compute stream);
     #      the same kernels timed back to back on cold slots, without the token loop, are listed beside it
     kern = {}
-    for which, name in ((0, "expert_gateup_gemv"), (3, "pure_read_of_the_same_bytes"), (1, "expert_down_combine_gemv"),
-                        (2, "router")):
+    mfma = wl.dtype == "bf16" and B >= 16          # the kernels a batch of this size runs on
+    which_list = [(0, "expert_gateup_gemv"), (3, "pure_read_of_the_same_bytes"), (1, "expert_down_combine_gemv"),
+                  (2, "router")] + ([(4, "expert_gateup_mfma"), (5, "expert_down_mfma")] if mfma else [])
+    for which, name in which_list:
         ms, nbytes = prof_eng.time_kernel(which, args.kernel_reps)
         kern[name] = {"us_per_launch": ms * 1e3, "bytes_per_launch": nbytes, "gbs": nbytes / (ms / 1e3) / 1e9}
     prof_eng.close()
-    dom = kern["expert_gateup_gemv"]
+    dom_name = "expert_gateup_mfma" if mfma else "expert_gateup_gemv"
+    dom = kern[dom_name]
     roofline = {"bound": "hbm",
-                "kernel": "gateup_b1_kernel (expert W_gate/W_up GEMV + SwiGLU, batch 1)" if B == 1 else "gate/up expert kernel (batch 1 shape)",
+                "kernel": ("expert_mfma_kernel<gate/up> (W_gate/W_up tiles + SwiGLU on the matrix cores, batch %d over %d resident experts)"
+                           % (B, dom["bytes_per_launch"] // (2 * wl.inter * H * wl.elem_bytes))) if mfma else
+                          ("gateup_b1 kernels (expert W_gate/W_up GEMV + SwiGLU, batch 1)" if B == 1 else "gate/up expert kernel (batch 1 shape)"),
                 "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dom["gbs"] / HBM_PEAK_GBS,
                 "traffic": PMC_TRAFFIC_BYTES.get(wl.name) if not reduced else None, "launches_timed": args.kernel_reps, "bytes_per_launch": dom["bytes_per_launch"],
                 "us_per_launch": dom["us_per_launch"],
                 "how": "two HIP events on the compute stream around back-to-back launches, each on the slots of the next layer",
-                "other_kernels": {k: v for k, v in kern.items() if k != "expert_gateup_gemv"},
+                "other_kernels": {k: v for k, v in kern.items() if k != dom_name},
                 "in_token_loop_event_pairs": {m: {"us_per_launch": breakdown[m]["gateup_us_per_launch_in_flow"],
                                                    "gbs": breakdown[m]["gateup_gbs_in_flow"]} for m in breakdown},
                 "in_token_loop_launches": gu_n}
@@ -210,7 +215,7 @@ def main():
     #      hold the event records and the residual driver); layers taken as alike.  Against the reduction
     #      measured between the two un-instrumented modes.
     od = breakdown["on_demand"]
-    kernel_ms = L * (2 * kern["router"]["us_per_launch"] + dom["us_per_launch"] +
+    kernel_ms = L * (2 * kern["router"]["us_per_launch"] + kern["expert_gateup_gemv"]["us_per_launch"] +
                      kern["expert_down_combine_gemv"]["us_per_launch"]) / 1e3 if B == 1 else None
     tpot_model = {"copy_ms_per_token": od["copy_ms_per_token"],
                   "compute_ms_per_token_kernels_back_to_back": kernel_ms,

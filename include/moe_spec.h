@@ -219,9 +219,11 @@ const char *moe_spec_last_error(const moe_spec_ctx *ctx);
  * compute stream between two timing events, each launch on the slots of the next layer in turn
  * (so that no launch finds its weights in a cache), executing k resident slots per launch for a
  * batch of one.  which: 0 = gate/up GEMV + SwiGLU, 1 = down GEMV + combine, 2 = router (true routing),
- * 3 = a kernel that only reads the gate/up bytes of the same slots (what streaming alone reaches).
+ * 3 = a kernel that only reads the gate/up bytes of the same slots (what streaming alone reaches),
+ * 4 / 5 = the matrix-core gate/up / down kernels (bf16 only) on a batch of max_batch tokens whose
+ * k*max_batch positions are dealt round-robin over min(S, E, k*max_batch) resident slots.
  * Writes the mean milliseconds per launch and the weight bytes one launch reads.
- * The slot contents are whatever the cache holds; outputs go to scratch. */
+ * The slot contents are whatever the cache holds; outputs go to scratch.  Not inside a decode step. */
 int moe_spec_time_kernel(moe_spec_ctx *ctx, int which, int reps, double *ms_per_launch,
                          int64_t *bytes_per_launch);
 

@@ -380,11 +380,13 @@ struct MfmaStep {
 // tokens, 64 positions per grid plane blockIdx.z.  Weights are read with ordinary loads: a lane's
 // two 16-byte loads of a step take alternate quarters of the same 128-byte lines, and the planes
 // of an expert share its weights through the caches; streaming loads measured 8-10 % slower here.
-template <bool GATEUP, int NT>
+template <bool GATEUP, int NT, int KSPLIT>
 __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a, const ActiveList act,
                                                              const uint16_t *act_q, uint16_t *hq_out) {
   __shared__ int list[kMaxBatch];
   __shared__ int n_list;
+  // partial accumulators of the wavefronts that share a tile: [wave][token tile][gate | up][register][lane]
+  __shared__ float partial[KSPLIT > 1 ? kWaves : 1][NT][GATEUP ? 2 : 1][4][kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int m = lane & 15, g = lane >> 4;
   const int K = GATEUP ? a.H : a.I;            // reduction length
@@ -403,9 +405,19 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
     gather_tokens(a.exec_ids, a.B * a.k, e, list, &n_list, tid);
     n = n_list;
   }
-  const int row_base = (blockIdx.x * kWaves + wave) * 16;
-  if (row_base >= R || n == 0) return;
+  // KSPLIT wavefronts share 16 output rows: they split the reduction dimension into equal parts
+  // (whole 64-column steps) and add their partial tiles in LDS.  Many short chains of dependent
+  // loads that start at different columns keep HBM busier than few long ones that walk their rows
+  // in step: a read-only probe of this access pattern reaches 6.2 TB/s with four wavefronts per 16
+  // rows against 4.6 TB/s with one.  Short reductions are not split: the launcher picks KSPLIT.
+  const int row_base = (blockIdx.x * (kWaves / KSPLIT) + wave / KSPLIT) * 16;
+  const int part = wave % KSPLIT;
+  if (n == 0) return;                          // the same for the whole workgroup
+  const bool rows_inside = row_base < R;       // a workgroup's last tiles may lie past the matrix
+  if (KSPLIT == 1 && !rows_inside) return;     // nothing to share, nobody waits for this wavefront
   const int ntiles = (n + 15) / 16;
+  const int k_part = (K + KSPLIT * 64 - 1) / (KSPLIT * 64) * 64;
+  const int k_begin = part * k_part, k_end = rows_inside ? min(K, k_begin + k_part) : k_begin;
   const int my_row = min(row_base + m, R - 1);
   const uint16_t *p0 = wbase + (GATEUP ? size_t(0) : size_t(2) * a.I * a.H) + size_t(my_row) * K;
   const uint16_t *p1 = p0 + size_t(a.I) * a.H;             // W_up row (GATEUP only)
@@ -423,11 +435,11 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
 #pragma unroll
   for (int t = 0; t < NT; ++t) { acc0[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; acc1[t] = f32x4_t{0.f, 0.f, 0.f, 0.f}; }
 
-  // columns past K load nothing and contribute zeros, so the two-stage loop below may run one
-  // step beyond the end
+  // columns past the wavefront's quarter load nothing and contribute zeros, so the staged loop
+  // below may run one step beyond the end
   auto fetch = [&](int k0, MfmaStep<GATEUP, NT> &st) {
     const int kk = k0 + 16 * g;
-    const bool v0 = kk < K, v1 = kk + 8 < K;
+    const bool v0 = kk < k_end, v1 = kk + 8 < k_end;
     st.w0[0] = load_bf16x8(p0 + kk, v0);
     st.w0[1] = load_bf16x8(p0 + kk + 8, v1);
     if (GATEUP) { st.w1[0] = load_bf16x8(p1 + kk, v0); st.w1[1] = load_bf16x8(p1 + kk + 8, v1); }
@@ -453,26 +465,58 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
     }
   };
   MfmaStep<GATEUP, NT> even, odd;              // the loads of one step are in flight during the other's MFMAs
-  fetch(0, even);
-  for (int k0 = 0; k0 < K; k0 += 128) {
+  fetch(k_begin, even);
+  for (int k0 = k_begin; k0 < k_end; k0 += 128) {
     fetch(k0 + 64, odd);
     multiply(even);
     fetch(k0 + 128, even);
     multiply(odd);
   }
 
+  if (KSPLIT > 1) {
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      if (t < ntiles) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          partial[wave][t][0][i][lane] = acc0[t][i];
+          if (GATEUP) partial[wave][t][GATEUP ? 1 : 0][i][lane] = acc1[t][i];
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  // Of the wavefronts that share a tile, number p finishes token tiles p, p + KSPLIT, ...  The
+  // accumulator layout is as the MFMA left it: lane = token column lane % 16, rows 4 (lane / 16) .. + 3.
   const int r0 = row_base + 4 * g;             // this lane's four output rows, all inside or all outside
   if (r0 >= R) return;
+  const int w0 = wave - part;                  // first of the wavefronts that share this tile
 #pragma unroll
   for (int t = 0; t < NT; ++t) {
-    if (t < ntiles && bvalid[t]) {
+    if (t % KSPLIT == part && t < ntiles && bvalid[t]) {
+      float s0[4], s1[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (KSPLIT == 1) {
+          s0[i] = acc0[t][i];
+          s1[i] = acc1[t][i];
+        } else {
+          s0[i] = 0.f;
+          s1[i] = 0.f;
+#pragma unroll
+          for (int p = 0; p < KSPLIT; ++p) {
+            s0[i] += partial[w0 + p][t][0][i][lane];
+            if (GATEUP) s1[i] += partial[w0 + p][t][GATEUP ? 1 : 0][i][lane];
+          }
+        }
+      }
       const int f = list[t * 16 + m];
       if (GATEUP) {
         uint16_t q[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const float gv = acc0[t][i], uv = acc1[t][i];
-          const float hv = round_to_bf16(gv / (1.f + expf(-gv)) * uv);
+          const float hv = round_to_bf16(s0[i] / (1.f + expf(-s0[i])) * s1[i]);
           q[i] = uint16_t(__float_as_uint(hv) >> 16);
         }
         uint2 packed;
@@ -480,8 +524,7 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
         packed.y = uint32_t(q[2]) | (uint32_t(q[3]) << 16);
         *reinterpret_cast<uint2 *>(hq_out + size_t(f) * R + r0) = packed;
       } else {
-        *reinterpret_cast<float4 *>(a.y + size_t(f) * R + r0) =
-            make_float4(acc0[t][0], acc0[t][1], acc0[t][2], acc0[t][3]);
+        *reinterpret_cast<float4 *>(a.y + size_t(f) * R + r0) = make_float4(s0[0], s0[1], s0[2], s0[3]);
       }
     }
   }
@@ -684,20 +727,33 @@ void launch_down_combine_b1(const ExpertArgs &a, const ActiveList &act, hipStrea
   else launch_down_combine_b1_n<WT, 4, 4>(a, act, st);
 }
 
+template <bool GATEUP, int KSPLIT>
+hipError_t launch_expert_mfma_k(const ExpertArgs &a, const ActiveList &act, const uint16_t *act_q, uint16_t *hq,
+                                hipStream_t st) {
+  const int rows = GATEUP ? a.I : a.H;
+  const int rows_per_wg = 16 * kWaves / KSPLIT;
+  const int planes = a.pos_list ? (a.list_tokens + kMaxBatch - 1) / kMaxBatch : 1;
+  const dim3 grid((rows + rows_per_wg - 1) / rows_per_wg, act.n, planes), block(kBlock);
+  const int nt = a.pos_list ? (std::min(a.list_tokens, kMaxBatch) + 15) / 16 : (a.B + 15) / 16;
+  switch (nt) {
+    case 1: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 1, KSPLIT>), grid, block, 0, st, a, act, act_q, hq); break;
+    case 2: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 2, KSPLIT>), grid, block, 0, st, a, act, act_q, hq); break;
+    case 3: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 3, KSPLIT>), grid, block, 0, st, a, act, act_q, hq); break;
+    default: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 4, KSPLIT>), grid, block, 0, st, a, act, act_q, hq); break;
+  }
+  return hipGetLastError();
+}
+
+// Wavefronts per 16-row tile by the length of the reduction: each should still walk at least
+// eight 64-column steps, below that the shared start-up (token lists, partial sums) outweighs
+// what the extra parallelism wins.
 template <bool GATEUP>
 hipError_t launch_expert_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *act_q, uint16_t *hq,
                               hipStream_t st) {
-  const int rows = GATEUP ? a.I : a.H;
-  const int planes = a.pos_list ? (a.list_tokens + kMaxBatch - 1) / kMaxBatch : 1;
-  const dim3 grid((rows + 16 * kWaves - 1) / (16 * kWaves), act.n, planes), block(kBlock);
-  const int nt = a.pos_list ? (std::min(a.list_tokens, kMaxBatch) + 15) / 16 : (a.B + 15) / 16;
-  switch (nt) {
-    case 1: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 1>), grid, block, 0, st, a, act, act_q, hq); break;
-    case 2: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 2>), grid, block, 0, st, a, act, act_q, hq); break;
-    case 3: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 3>), grid, block, 0, st, a, act, act_q, hq); break;
-    default: hipLaunchKernelGGL((expert_mfma_kernel<GATEUP, 4>), grid, block, 0, st, a, act, act_q, hq); break;
-  }
-  return hipGetLastError();
+  const int steps = ((GATEUP ? a.H : a.I) + 63) / 64;
+  if (steps >= 32) return launch_expert_mfma_k<GATEUP, 4>(a, act, act_q, hq, st);
+  if (steps >= 16) return launch_expert_mfma_k<GATEUP, 2>(a, act, act_q, hq, st);
+  return launch_expert_mfma_k<GATEUP, 1>(a, act, act_q, hq, st);
 }
 
 template <typename K>

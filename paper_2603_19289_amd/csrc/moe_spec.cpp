@@ -1058,8 +1058,10 @@ int moe_spec_reset(moe_spec_ctx *c) {
 
 int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_launch, int64_t *bytes_per_launch) {
   if (!c) return MOE_SPEC_EINVAL;
-  if (which < 0 || which > 3 || reps < 1 || !ms_per_launch || !bytes_per_launch)
+  if (which < 0 || which > 5 || reps < 1 || !ms_per_launch || !bytes_per_launch)
     return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
+  if (which >= 4 && c->cfg.dtype != MOE_SPEC_BF16) return c->fail(MOE_SPEC_ESTATE, "the matrix-core kernels need bf16 weights");
+  if (c->token_open) return c->fail(MOE_SPEC_ESTATE, "time_kernel inside a decode step");
   const moe_spec_config &cfg = c->cfg;
   const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter;
   const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
@@ -1093,6 +1095,24 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   ra.diag = c->at<LayerDiag>(c->lay.diag);
   ra.B = 1; ra.H = H; ra.E = E; ra.k = k; ra.eps = cfg.rms_eps; ra.bf16 = xa.bf16;
   const bool fast = b1_supported(H, cfg.dtype);
+  // matrix-core kernels: a full batch whose positions are dealt round-robin over as many resident
+  // slots as a cache wave can hold (a token's k experts stay distinct because n_act >= k)
+  const int Bm = cfg.max_batch;
+  const int n_act = std::min({cfg.slots_per_layer, E, Bm * k});
+  ActiveList act_m{};
+  ExpertArgs xm = xa;
+  if (which >= 4) {
+    std::vector<int32_t> tab(size_t(Bm) * k);
+    for (size_t f = 0; f < tab.size(); ++f) tab[f] = int32_t(f % n_act);
+    act_m.n = n_act;
+    for (int j = 0; j < n_act; ++j) { act_m.expert[j] = int16_t(j); act_m.slot[j] = int16_t(j); }
+    if ((e = hipMemcpy(c->arena + c->lay.pend_ids[0], tab.data(), tab.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+      (void)hipEventDestroy(t0); (void)hipEventDestroy(t1);
+      return c->hip_fail(e, "upload ids");
+    }
+    xm.exec_ids = c->at<int32_t>(c->lay.pend_ids[0]);
+    xm.B = Bm;
+  }
   hipError_t le = hipSuccess;
   for (int pass = 0; pass < 2 && le == hipSuccess; ++pass) {      // pass 0 warms up
     const int n = pass == 0 ? std::min(reps, 4) : reps;
@@ -1103,6 +1123,8 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
       if (which == 0) le = fast ? launch_gateup_b1(xa, act, cfg.dtype, c->compute) : launch_gateup(xa, act, cfg.dtype, c->compute);
       else if (which == 1) le = fast ? launch_down_combine_b1(xa, act, cfg.dtype, c->compute) : launch_down(xa, act, cfg.dtype, c->compute);
       else if (which == 3) le = launch_stream_read(xa, act, c->compute);
+      else if (which == 4) { xm.pool = xa.pool; le = launch_gateup_mfma(xm, act_m, c->at<uint16_t>(c->lay.s_q), c->at<uint16_t>(c->lay.h), c->compute); }
+      else if (which == 5) { xm.pool = xa.pool; le = launch_down_mfma(xm, act_m, c->at<uint16_t>(c->lay.h), c->compute); }
       else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
     }
     if (pass == 1 && le == hipSuccess) le = hipEventRecord(t1, c->compute);
@@ -1117,6 +1139,8 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   *ms_per_launch = double(ms) / reps;
   *bytes_per_launch = which == 0 || which == 3 ? int64_t(k) * 2 * I * H * wbytes
                     : which == 1 ? int64_t(k) * I * H * wbytes
+                    : which == 4 ? int64_t(n_act) * 2 * I * H * wbytes
+                    : which == 5 ? int64_t(n_act) * I * H * wbytes
                                  : int64_t(E) * H * wbytes;
   return MOE_SPEC_OK;
 }

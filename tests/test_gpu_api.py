@@ -221,3 +221,31 @@ def test_accumulated_default_vectors_match_the_checker(dtype, B, mode):
     buf = torch.empty((wl.n_experts, wl.hidden), device="cuda")
     assert M.lib().moe_spec_read_default_vectors(eng.ctx, 0, buf.data_ptr(), None) == M.ESTATE
     eng.close()
+
+
+def test_time_kernel_modes_and_their_byte_counts():
+    # the measurement aid: every mode runs, reports the weight bytes of its launch, and refuses what it cannot do
+    wl = small_workload(n_layers=3, hidden=128, n_experts=12, top_k=3, inter=96, dtype="bf16", batch=20, slots=5)
+    res, ex, _ = build(wl)
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex)
+    w = 2
+    want = {0: wl.top_k * 2 * wl.inter * wl.hidden * w, 1: wl.top_k * wl.inter * wl.hidden * w,
+            2: wl.n_experts * wl.hidden * w, 3: wl.top_k * 2 * wl.inter * wl.hidden * w,
+            4: 5 * 2 * wl.inter * wl.hidden * w, 5: 5 * wl.inter * wl.hidden * w}     # 5 = min(S, E, B*k) slots
+    for which, nbytes in want.items():
+        ms, got = eng.time_kernel(which, 6)
+        assert ms > 0 and got == nbytes, (which, ms, got, nbytes)
+    with pytest.raises(M.MoeSpecError):
+        eng.time_kernel(6, 1)
+    eng.begin_token()
+    with pytest.raises(M.MoeSpecError) as ei:
+        eng.time_kernel(0, 1)                    # not inside a decode step
+    assert ei.value.code == M.ESTATE
+    eng.close()
+    wl32 = small_workload(dtype="f32")
+    res, ex, _ = build(wl32)
+    eng = _engine(wl32, M.MODE_ON_DEMAND, res, ex)
+    with pytest.raises(M.MoeSpecError) as ei:
+        eng.time_kernel(4, 1)                    # matrix-core kernels are bf16 only
+    assert ei.value.code == M.ESTATE
+    eng.close()
