@@ -49,7 +49,7 @@ def parse():
                    help="also time the prefill step on a prompt of P tokens (every expert of every layer streamed); 0 = skip")
     p.add_argument("--kernel-reps", type=int, default=480)
     p.add_argument("--copy-engine", choices=["auto", "kernel", "dma", "dma2"], default="auto",
-                   help="auto: each mode gets the engine that is fastest for it (speculative: four DMA queues, "
+                   help="auto: each mode gets the engine that is fastest for it (speculative: two DMA queues, "
                         "on-demand: gather-copy kernel)")
     return p.parse_args()
 
@@ -89,7 +89,7 @@ def main():
     log(f"[bench] {wl.name}: pool {L * wl.n_experts * wl.expert_bytes / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
 
     codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
-    # four DMA queues pay off from a few MB per expert on; below that their set-up latency dominates
+    # the second DMA queue pays off from a few MB per expert on; below that their set-up latency dominates
     spec_auto = "dma2" if wl.expert_bytes >= (4 << 20) else "kernel"
     engine_names = {"speculative": spec_auto if args.copy_engine == "auto" else args.copy_engine,
                     "on_demand": "kernel" if args.copy_engine == "auto" else args.copy_engine}

@@ -72,9 +72,9 @@ typedef struct {
                                        1: one gather-copy kernel per request that reads the pinned
                                           pool directly (a few workgroups; keeps the link busier but
                                           slows kernels that run beside it);
-                                       2: experts dealt round-robin to four DMA queues (copy_stream plus
-                                          three streams the library creates), so that one transfer's
-                                          set-up hides behind another's data */
+                                       2: experts dealt alternately to two DMA queues (copy_stream and one
+                                          stream the library creates), so that one transfer's set-up hides
+                                          behind the other's data */
   int32_t predict_signal;           /* what layer l+1's router is run on to predict: 0 the quasi-hidden
                                        state q_l (the method); 1 the normalised residual s_l as it is
                                        (the baseline signal of Sec. 3.3) */

@@ -37,7 +37,7 @@ struct Pool {                       // one layer's slot cache (least recently us
   long clock = 0;
 };
 
-constexpr int kDmaQueues = 4;        // copy_engine 2: the caller's copy stream plus three more
+constexpr int kDmaQueues = 2;        // copy_engine 2: the caller's copy stream plus one more
 
 struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 gate/up kernel
 
