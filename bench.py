@@ -187,7 +187,7 @@ def main():
     #      mean launch duration inside the two instrumented token loops (event pairs on the compute stream);
     #      the same kernels timed back to back on cold slots, without the token loop, are listed beside it
     kern = {}
-    mfma = wl.dtype == "bf16" and B >= 16          # the kernels a batch of this size runs on
+    mfma = wl.dtype == "bf16" and B >= 2          # the kernels a batch of this size runs on
     which_list = [(0, "expert_gateup_gemv"), (3, "pure_read_of_the_same_bytes"), (1, "expert_down_combine_gemv"),
                   (2, "router")] + ([(4, "expert_gateup_mfma"), (5, "expert_down_mfma")] if mfma else [])
     for which, name in which_list:

@@ -347,9 +347,10 @@ __global__ __launch_bounds__(kBlock) void down_combine_b1_kernel(const ExpertArg
 }
 
 // ---------------------------------------------------------------------------------------------
-// Matrix-core kernels for decode batches of 16 and more (bf16 weights): with that many tokens
-// the vector ALUs, not HBM, would limit a GEMV, so the expert FFN is done as 16x16x32 bf16 MFMA
-// tiles.  A operand = 16 weight rows, B operand = up to 16 tokens routed to the expert, K walks
+// Matrix-core kernels for decode batches of two and more (bf16 weights) and for prefill: the
+// expert FFN as 16x16x32 bf16 MFMA tiles.  The launches stay HBM-bound, but one weight fragment
+// meets up to 16 tokens per instruction, where the general kernels above fetch every token's
+// activations from LDS for every weight chunk and are LDS-bound from a few tokens on.  A operand = 16 weight rows, B operand = up to 16 tokens routed to the expert, K walks
 // the reduction dimension 64 columns per step: lane (m, g) = (lane % 16, lane / 16) loads the 32
 // contiguous bytes at column k0 + 16 g of row m (so four lanes cover one 128-byte line) and
 // feeds the first 8 columns to one MFMA and the next 8 to a second one; the B operand is read
@@ -790,7 +791,7 @@ hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hi
   return dtype == 1 ? launch_down_t<uint16_t>(a, act, st) : launch_down_t<float>(a, act, st);
 }
 
-// bf16 weights, batch >= 16: s_q is s_l as bf16 [B,H]; hq (bf16 [B,k,I]) is written by the gate/up
+// bf16 weights, batch >= kMfmaMinBatch: s_q is s_l as bf16 [B,H]; hq (bf16 [B,k,I]) is written by the gate/up
 // launch and read by the down launch.
 hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
                               hipStream_t st) {

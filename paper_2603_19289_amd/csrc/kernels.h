@@ -122,7 +122,7 @@ hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const 
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);
 hipError_t launch_expert_lists(const int32_t *ids, int tokens, int k, int E, int32_t *pos, int32_t *count,
                                hipStream_t st);      // pos [E, tokens], count [E]
-constexpr int kMfmaMinBatch = 16;     // decode batches from here on use the matrix-core expert kernels
+constexpr int kMfmaMinBatch = 2;      // bf16 decode batches from here on use the matrix-core expert kernels
 // Running sums for the default vectors: sum[e,:] += y[f,:] and cnt[e] += 1 for every position f whose
 // expert ids[f] is in the launch's active list; means = sum / max(cnt, 1).
 hipError_t launch_accumulate_defaults(const ExpertArgs &a, const ActiveList &act, double *sum,

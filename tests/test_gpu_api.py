@@ -188,7 +188,8 @@ def test_per_layer_diagnostics_match_the_checker(signal, dtype, B):
     eng.close()
 
 
-@pytest.mark.parametrize("dtype,B,mode", [("f32", 1, M.MODE_ON_DEMAND), ("bf16", 3, M.MODE_SPECULATIVE), ("bf16", 20, M.MODE_ON_DEMAND)])
+@pytest.mark.parametrize("dtype,B,mode", [("f32", 1, M.MODE_ON_DEMAND), ("bf16", 1, M.MODE_SPECULATIVE), ("f32", 3, M.MODE_ON_DEMAND),
+                                           ("bf16", 3, M.MODE_SPECULATIVE), ("bf16", 20, M.MODE_ON_DEMAND)])
 def test_accumulated_default_vectors_match_the_checker(dtype, B, mode):
     # the offline statistic behind d_{l,e}: mean un-gated output per executed expert, with counts
     wl = small_workload(n_layers=3, hidden=264, n_experts=12, top_k=3, inter=200, dtype=dtype, batch=B,
