@@ -71,8 +71,6 @@ __device__ __forceinline__ float dot_chunk(const float4 &w, const float4 &a, flo
   return acc + w.w * a.w;
 }
 
-__device__ __forceinline__ void zero_chunk(uint4 &v) { v = make_uint4(0u, 0u, 0u, 0u); }
-__device__ __forceinline__ void zero_chunk(float4 &v) { v = make_float4(0.f, 0.f, 0.f, 0.f); }
 
 // float -> nearest bfloat16 (ties to even) -> float; finite inputs.
 __device__ __forceinline__ float round_to_bf16(float x) {

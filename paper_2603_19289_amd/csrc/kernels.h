@@ -82,7 +82,7 @@ struct ExpertArgs {
   float *h;                   // [B,k,I] SwiGLU products
   float *y;                   // [B,k,H] un-gated expert outputs
   float *out;                 // [B,H]
-  int B, k, H, I, bf16, tok_tile;
+  int B, k, H, I, bf16;
   // matrix-core kernels over more than one decode batch (prefill): positions grouped by expert as
   // written by launch_expert_lists for list_tokens tokens; null: the [B,k] table exec_ids is searched
   const int32_t *pos_list;    // [E, list_stride]
