@@ -163,7 +163,9 @@ int moe_spec_begin_token(moe_spec_ctx *ctx);
 /* One MoE block.  r_dev [batch,H] float (post-attention residual r_l), out_dev [batch,H] float
  * (O_l, valid in compute-stream order).  Layers must be stepped 0,1,...,L-1 after begin_token with
  * the same batch (MOE_SPEC_ESTATE otherwise, also when a layer's tables or experts were never
- * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host. */
+ * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host.
+ * Non-finite activations do not fault: a logit that is not a number ranks as minus infinity, so the k
+ * ids stay distinct and inside [0, E); the row's gates and outputs are NaN. */
 int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
                         const moe_spec_step_outputs *outs);
 

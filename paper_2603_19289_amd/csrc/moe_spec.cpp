@@ -343,6 +343,15 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
 
+  // Expert ids handed over by a routing kernel index host tables: refuse anything outside [0, E).
+  int check_ids(const int32_t *ids, int n) {
+    for (int i = 0; i < n; ++i)
+      if (ids[i] < 0 || ids[i] >= cfg.n_experts)
+        return fail(MOE_SPEC_EHIP, "the routing kernel handed over expert id %d (position %d), outside [0, %d)",
+                    ids[i], i, cfg.n_experts);
+    return MOE_SPEC_OK;
+  }
+
   static std::vector<int> sorted_union(const int32_t *ids, int n) {
     std::vector<int> u(ids, ids + n);
     std::sort(u.begin(), u.end());
@@ -691,6 +700,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   } else {
     int rc = c->wait_mailbox(c->mb_true, ticket_true);
     if (rc) return rc;
+    if ((rc = c->check_ids(c->mb_true->ids, batch * k))) return rc;
     exec_union = moe_spec_ctx::sorted_union(c->mb_true->ids, batch * k);
     exec_ids_host.assign(c->mb_true->ids, c->mb_true->ids + batch * k);
     exec_ids_dev = c->at<int32_t>(c->lay.true_ids);
@@ -780,6 +790,7 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   if (do_pred && prefetching) {
     int rc = c->wait_mailbox(c->mb_next, ticket_next);
     if (rc) return rc;
+    if ((rc = c->check_ids(c->mb_next->ids, batch * k))) return rc;
     c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
     c->pending_ids.assign(c->mb_next->ids, c->mb_next->ids + batch * k);
     std::vector<int> req(c->pending_union.begin(),

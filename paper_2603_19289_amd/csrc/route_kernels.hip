@@ -80,7 +80,12 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid, int
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int i = r * kWave + lane;
-      key[r] = i < a.E ? load_coherent(a.z + size_t(b) * a.E + i) : -INFINITY;
+      // A logit that is not a number (a non-finite input row) sorts as minus infinity: comparisons
+      // with NaN are all false, ranks would collide, and slots of the top-k table would keep whatever
+      // the LDS held - ids far outside [0, E) that later kernels use as row indices.  With this the
+      // order (logit descending, index ascending) is total whatever the input, and ids stay in range.
+      const double zi = i < a.E ? load_coherent(a.z + size_t(b) * a.E + i) : -INFINITY;
+      key[r] = zi == zi ? zi : -INFINITY;
     }
     for (int i = tid; i < kMaxExperts; i += kRouteBlock) sh.rank[i] = 0;
     __syncthreads();

@@ -105,7 +105,18 @@ class Engine:
         if sync_input:
             self.compute.wait_stream(torch.cuda.current_stream(self.dev))
         M.moe_spec_layer_step(self.ctx, layer, r.data_ptr(), B, out.data_ptr(), outs)
+        if sync_input:
+            self._hand_back(r, out, *(bufs.values() if bufs else ()))
         return out, bufs
+
+    def _hand_back(self, *tensors):
+        """The tensors were allocated on the caller's stream but are read or written by kernels on the
+        compute stream: tell torch's allocator so (a freed block must not be reused before those
+        kernels ran) and make the caller's stream wait for them."""
+        for t in tensors:
+            if t is not None:
+                t.record_stream(self.compute)
+        torch.cuda.current_stream(self.dev).wait_stream(self.compute)
 
     def prefill_layer_step(self, layer: int, r: torch.Tensor, out: Optional[torch.Tensor] = None, want_ids=False,
                            sync_input=True):
@@ -122,13 +133,20 @@ class Engine:
             self.compute.wait_stream(torch.cuda.current_stream(self.dev))
         M.moe_spec_prefill_layer_step(self.ctx, layer, r.data_ptr(), P, out.data_ptr(),
                                       ids.data_ptr() if want_ids else None, gates.data_ptr() if want_ids else None)
+        if sync_input:
+            self._hand_back(r, out, ids, gates)
         return out, ids, gates
 
     def advance(self, r, out, eps, a, b, r_next=None):
         if r_next is None:
             r_next = torch.empty_like(r)
+        foreign = torch.cuda.current_stream(self.dev) != self.compute     # the caller works on another stream
+        if foreign:
+            self.compute.wait_stream(torch.cuda.current_stream(self.dev))
         M.moe_spec_synth_advance(self.compute.cuda_stream, r.data_ptr(), out.data_ptr(), eps.data_ptr(),
                                  a, b, r.shape[0], r.shape[1], r_next.data_ptr())
+        if foreign:
+            self._hand_back(r, out, eps, r_next)
         return r_next
 
     def stats(self) -> dict:

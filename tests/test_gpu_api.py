@@ -250,3 +250,40 @@ def test_time_kernel_modes_and_their_byte_counts():
         eng.time_kernel(4, 1)                    # matrix-core kernels are bf16 only
     assert ei.value.code == M.ESTATE
     eng.close()
+
+
+@pytest.mark.parametrize("dtype,B", [("f32", 1), ("bf16", 1), ("bf16", 6)])
+def test_non_finite_inputs_keep_expert_ids_in_range(dtype, B):
+    # NaN or infinite activations give NaN logits; the ranking must still hand out k distinct ids inside
+    # [0, E) (they index weight rows and host tables), outputs are NaN, and the context stays usable
+    wl = small_workload(n_layers=3, hidden=128, n_experts=70, top_k=4, inter=64, dtype=dtype, batch=B, slots=8, tokens=2)
+    res, ex, model = build(wl, "random")
+    x0, eps = W.make_inputs(wl)
+    for mode in (M.MODE_SPECULATIVE, M.MODE_ON_DEMAND):
+        eng = _engine(wl, mode, res, ex)
+        try:
+            for bad in (float("nan"), float("inf")):
+                eng.begin_token()
+                r = torch.from_numpy(x0[0]).cuda()
+                r[0, 5] = bad
+                for l in range(wl.n_layers):
+                    out, ids = eng.layer_step(l, r, want_ids=True)
+                    torch.cuda.synchronize()
+                    for key in ("true_ids", "exec_ids") + (("next_ids",) if l + 1 < wl.n_layers else ()):
+                        got = ids[key].cpu().numpy()
+                        assert ((got >= 0) & (got < wl.n_experts)).all(), (key, got)
+                        assert all(len(set(row)) == wl.top_k for row in got.tolist()), (key, got)
+                    assert torch.isnan(out[0]).all()
+                    r = r + out
+            # a clean token afterwards matches the checker again
+            eng.reset()
+            orc = O.MoEOracle(model, mode, wl.slots)
+            trace = O.run_tokens(orc, x0[:1], make_advance(wl, eps))
+            eng.begin_token()
+            for l in range(wl.n_layers):
+                r_np, want = trace[0][l]
+                out, ids = eng.layer_step(l, torch.from_numpy(r_np.astype(np.float32)).cuda(), want_ids=True)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), want.exec_ids)
+        finally:
+            eng.close()
