@@ -19,8 +19,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per gate/up launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a plain
-# copy of known size (profiles/bench_c2_qwen3_pmc_hbm_traffic.md); only for the workload it was measured on
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a
+# plain copy of known size (profiles/bench_c2_qwen3_pmc_hbm_traffic.md, profiles/bench_c5_qwen3_b32_kernel_trace_and_pmc.md);
+# only for the workloads it was measured on
 PMC_TRAFFIC_BYTES = {"c2_qwen3_30b_a3b": 50487521, "c5_qwen3_b32": 304003275}
 LINK_PEAK_GBS = 64.0           # PCIe Gen5 x16, one direction, nominal
 
