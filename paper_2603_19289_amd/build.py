@@ -11,12 +11,24 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x",
          "-Wall", "-Wno-unused-function"]
 
 
+DEMO = os.path.join(HERE, "abi_demo")
+
+
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc] + FLAGS + [os.path.join(HERE, s) for s in SOURCES] + ["-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True, cwd=HERE)
+    # the plain C client of the library (C99, host compiler): shows that the header is C and that the
+    # boundary needs neither Python nor torch
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    demo = ["gcc", "-std=c99", "-O1", "-Wall", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include",
+            os.path.join(HERE, "csrc/abi_demo.c"), "-o", DEMO, f"-L{HERE}", "-lmoe_spec", f"-L{rocm}/lib",
+            "-lamdhip64", "-lm", "-Wl,-rpath,$ORIGIN", f"-Wl,-rpath,{rocm}/lib"]
+    if verbose:
+        print(" ".join(demo), flush=True)
+    subprocess.run(demo, check=True, cwd=HERE)
     return LIB
 
 
