@@ -92,3 +92,28 @@ def test_null_context_is_an_error_not_a_crash():
     assert lib.moe_spec_stats(None, None) == M.EINVAL
     assert lib.moe_spec_layer_step(None, 0, None, 1, None, None) == M.EINVAL
     lib.moe_spec_destroy(None)
+
+
+def test_prefill_entry_point_rejects_a_null_context():
+    assert M.lib().moe_spec_prefill_layer_step(None, 0, None, 1, None, None, None) == M.EINVAL
+
+
+def test_invalid_prefill_capacity_is_rejected():
+    cfg = good_config()
+    cfg.max_prefill_tokens = -1
+    assert M.moe_spec_arena_bytes(cfg) == 0
+    cfg.max_prefill_tokens = 1 << 20
+    assert M.moe_spec_arena_bytes(cfg) == 0
+    cfg.max_prefill_tokens = 0
+    small = M.moe_spec_arena_bytes(cfg)
+    cfg.max_prefill_tokens = 256
+    assert M.moe_spec_arena_bytes(cfg) > small           # the prefill buffers are part of the arena
+
+
+def test_bench_refuses_more_than_one_gpu(monkeypatch, capsys):
+    import bench
+    monkeypatch.setattr("sys.argv", ["bench.py", "--gpus", "2"])
+    with pytest.raises(SystemExit) as ei:
+        bench.main()
+    assert ei.value.code == 2
+    assert "ONE GPU" in capsys.readouterr().err
