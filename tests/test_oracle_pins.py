@@ -307,3 +307,24 @@ def test_tpot_model_invariants():
         assert abs(t_pf - sum(max(a, b) for a, b in zip(comp, copy))) < 1e-9
     t_ond, t_pf, _ = O.tpot_model([2.0] * 7, [2.0] * 7)
     assert t_ond / t_pf == 2.0
+
+
+# --------------------------------------------------------------------------------------
+# Expert block size against the paper's model table
+# --------------------------------------------------------------------------------------
+def test_expert_block_size_reproduces_the_papers_expert_memory():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "model_config.txt")
+    rows = [[f.strip() for f in line.split("|")] for line in open(path) if line.strip() and not line.startswith("#")]
+    assert len(rows) == 2
+    empty = np.zeros((0,))
+    for name, L, E, H, I, printed_gb in rows:
+        model = O.OracleModel(n_layers=int(L), hidden=int(H), n_experts=int(E), top_k=8, inter=int(I), dtype=O.DTYPE_BF16,
+                              router_w=empty, rms_gain=empty, dvecs=empty, experts=empty)
+        total_gib = model.expert_bytes * int(L) * int(E) / 2 ** 30
+        assert abs(total_gib - float(printed_gb)) <= 1.0, (name, total_gib)
+    # the benchmark workload has the first row's shapes, and the library's block size is the same number
+    from paper_2603_19289_amd import workload as W
+    wl = W.CONFIGS["c2_qwen3_30b_a3b"]
+    assert (wl.n_layers, wl.n_experts, wl.hidden, wl.inter) == (48, 128, 2048, 768)
+    assert wl.expert_bytes == 3 * 2048 * 768 * 2
