@@ -7,16 +7,11 @@ import torch
 
 from oracle import moe_oracle as O
 from paper_2603_19289_amd import workload as W
-from tests.helpers import build, make_advance, small_workload
+from tests.helpers import build, check_output, make_advance, small_workload
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
 MODES = {"on_demand": O.MODE_ON_DEMAND, "speculative": O.MODE_SPECULATIVE, "prefetch_hint": O.MODE_PREFETCH_HINT}
-
-
-def rel_err(got, want):
-    return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
 
 
 def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", prebuilt=None, oracle_kw=None,
@@ -34,7 +29,7 @@ def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", 
     orc = O.MoEOracle(model, mode, wl.slots, q_from_normalized=bool(q_from_normalized), **(oracle_kw or {}))
     trace = O.run_tokens(orc, x0, make_advance(wl, eps))
     eng = engine_for(wl, mode, res, ex, q_from_normalized=q_from_normalized, **engine_kw)
-    worst = 0.0
+    worst = worst_elem = 0.0
     try:
         for t in range(wl.tokens):
             eng.begin_token()
@@ -53,15 +48,14 @@ def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", 
                     np.testing.assert_allclose(ids["next_gates"].cpu().numpy(), want.next_gates, atol=2e-7, rtol=1e-6, err_msg=where)
                 else:
                     assert (ids["next_ids"].cpu().numpy() == -1).all(), where
-                err = rel_err(out.cpu().numpy().astype(np.float64), want.out).max()
-                worst = max(worst, err)
-                assert err <= TOL[wl.dtype], f"{where}: relative error {err:.3e}"
+                l2, elem = check_output(out.cpu().numpy(), want.out, wl.dtype, where)
+                worst, worst_elem = max(worst, l2), max(worst_elem, elem)
         st = eng.stats()
         for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes"):
             assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
     finally:
         eng.close()
-    print(f"[ok] worst relative error {worst:.3e}; hits {orc.stats.hits}/{orc.stats.predictions}; "
+    print(f"[ok] worst relative L2 error {worst:.3e}, worst element error {worst_elem:.3e} of the row RMS; hits {orc.stats.hits}/{orc.stats.predictions}; "
           f"cache {orc.stats.cache_hits} hits {orc.stats.cache_misses} misses", flush=True)
     return worst
 

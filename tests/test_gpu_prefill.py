@@ -11,16 +11,9 @@ import torch
 from oracle import moe_oracle as O
 from paper_2603_19289_amd import moe_spec as M
 from paper_2603_19289_amd import workload as W
-from tests.helpers import build, make_advance, small_workload
+from tests.helpers import build, check_output, make_advance, small_workload
 
 pytestmark = pytest.mark.gpu
-
-TOL = {"f32": 1e-5, "bf16": 2e-2}
-
-
-def rel_err(got, want):
-    return np.linalg.norm(got - want, axis=-1) / np.maximum(np.linalg.norm(want, axis=-1), 1e-30)
-
 
 def prompt_of(wl, P):
     """[P,H] first-layer residuals and [L,P,H] noise for the layer-to-layer update, from the seeded generators."""
@@ -39,7 +32,7 @@ def run_prefill(wl, P, max_batch, label, prebuilt=None, **engine_kw):
     r_np, eps = prompt_of(wl, P)
     orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
     eng = engine_for(wl, O.MODE_SPECULATIVE, res, ex, max_batch=max_batch, max_prefill_tokens=P + 3, **engine_kw)
-    worst = 0.0
+    worst = worst_elem = 0.0
     try:
         for l in range(wl.n_layers):
             want = orc.prefill_layer_step(l, r_np)
@@ -48,9 +41,8 @@ def run_prefill(wl, P, max_batch, label, prebuilt=None, **engine_kw):
             torch.cuda.synchronize()
             np.testing.assert_array_equal(ids.cpu().numpy(), want.true_ids, err_msg=f"layer {l}")
             np.testing.assert_allclose(gates.cpu().numpy(), want.true_gates, atol=2e-7, rtol=1e-6, err_msg=f"layer {l}")
-            err = rel_err(out.cpu().numpy().astype(np.float64), want.out).max()
-            worst = max(worst, err)
-            assert err <= TOL[wl.dtype], f"layer {l}: relative error {err:.3e}"
+            l2, elem = check_output(out.cpu().numpy(), want.out, wl.dtype, f"layer {l}")
+            worst, worst_elem = max(worst, l2), max(worst_elem, elem)
             r_np = W.advance_residual(wl, r_np, want.out, eps[l])
         st = eng.stats()
         for name in ("layer_steps", "cache_hits", "cache_misses", "h2d_bytes", "predictions"):
@@ -58,7 +50,7 @@ def run_prefill(wl, P, max_batch, label, prebuilt=None, **engine_kw):
         assert st["prefill_tokens"] == P * wl.n_layers
     finally:
         eng.close()
-    print(f"[ok] worst relative error {worst:.3e}", flush=True)
+    print(f"[ok] worst relative L2 error {worst:.3e}, worst element error {worst_elem:.3e} of the row RMS", flush=True)
 
 
 @pytest.mark.parametrize("copy_engine", [M.COPY_DMA, M.COPY_KERNEL, M.COPY_DMA2])
@@ -113,7 +105,7 @@ def test_default_vectors_calibrated_by_prefill(dtype):
                 want = orc.prefill_layer_step(l, r_np)
                 out, _, _ = eng.prefill_layer_step(l, torch.from_numpy(r_np.astype(np.float32)).to("cuda"))
                 torch.cuda.synchronize()
-                assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL[dtype]
+                check_output(out.cpu().numpy(), want.out, dtype, f"prompt of {P}, layer {l}")
                 r_np = W.advance_residual(wl, r_np, want.out, eps[l])
         for l in range(wl.n_layers):
             mean, counts = eng.read_default_vectors(l)
@@ -121,7 +113,7 @@ def test_default_vectors_calibrated_by_prefill(dtype):
             got, want = mean.cpu().numpy().astype(np.float64), orc.default_vectors(l)
             for e in range(wl.n_experts):
                 if counts[e]:
-                    assert np.linalg.norm(got[e] - want[e]) <= TOL[dtype] * np.linalg.norm(want[e]), (l, e)
+                    check_output(got[e], want[e], dtype, f"default vector of layer {l}, expert {e}")
                 else:
                     assert not got[e].any()
     finally:
@@ -150,7 +142,7 @@ def test_decode_after_prefill_starts_from_an_empty_cache(mode):
             want = orc.prefill_layer_step(l, r_np)
             out, _, _ = eng.prefill_layer_step(l, torch.from_numpy(r_np.astype(np.float32)).to("cuda"))
             torch.cuda.synchronize()
-            assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL["bf16"]
+            check_output(out.cpu().numpy(), want.out, "bf16", f"prefill layer {l}")
             r_np = W.advance_residual(wl, r_np, want.out, eps_p[l])
         trace = O.run_tokens(orc, x0[1:], lambda t, l, r, out: W.advance_residual(wl, r, out, eps[t + 1, l]))
         for t in range(len(trace)):
@@ -160,7 +152,7 @@ def test_decode_after_prefill_starts_from_an_empty_cache(mode):
                 out, ids = eng.layer_step(l, torch.from_numpy(r_l.astype(np.float32)).to("cuda"), want_ids=True)
                 torch.cuda.synchronize()
                 np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), want.exec_ids)
-                assert rel_err(out.cpu().numpy().astype(np.float64), want.out).max() <= TOL["bf16"]
+                check_output(out.cpu().numpy(), want.out, "bf16", f"decode token {t} layer {l}")
         st = eng.stats()
         for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes"):
             assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
