@@ -169,6 +169,26 @@ int moe_spec_begin_token(moe_spec_ctx *ctx);
 int moe_spec_layer_step(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
                         const moe_spec_step_outputs *outs);
 
+/* For callers that cannot allocate device memory and want the arena to hold nothing but state
+ * (code that runs where hipMalloc is forbidden, tight serving loops that size the arena once for
+ * the slot cache): the same layer step as moe_spec_layer_step, same arguments, same results bit for
+ * bit, but the scratch of the step (normalised inputs, router logits, true ids and gates, SwiGLU
+ * products, un-gated expert outputs, the estimator's intermediates: everything the kernels write
+ * and read back within one call) lives in a static device array inside the library instead of in
+ * the arena.  The array is MOE_SPEC_STATIC_SCRATCH_BYTES large, one copy per GPU, held until the
+ * process ends; its device address is looked up once per device by moe_spec_create.  The call
+ * allocates nothing on the device (no hipMalloc, no hipFree, no event creation).
+ * MOE_SPEC_EINVAL if the configuration's step scratch exceeds the array (it grows with
+ * max_batch * top_k * (inter + hidden)); MOE_SPEC_ESTATE for a context with profile = 1 (timing
+ * events are created on demand there) or when the current device is not the context's.
+ * Every context on a GPU shares that GPU's array, and the array keeps the previous call's
+ * contents: nothing in it has to start at zero (every word is written before it is read within a
+ * call), but two calls that overlap in time on one GPU (two contexts on different streams, or two
+ * host threads) race.  Calls of the two entry points may be mixed freely on one context. */
+#define MOE_SPEC_STATIC_SCRATCH_BYTES (8u << 20)
+int moe_spec_layer_step_static(moe_spec_ctx *ctx, int layer, const void *r_dev, int batch, void *out_dev,
+                               const moe_spec_step_outputs *outs);
+
 /* Prefill (paper: Sec. 5.2, prefill phase): one MoE block over all n_tokens prompt tokens at once.
  * Nothing is predicted: a prompt activates (nearly) every expert, so every expert of `layer` is
  * streamed from the host pool through the layer's slots, half of the slots receiving the next group

@@ -18,6 +18,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -26,7 +27,36 @@
 
 using namespace moe_spec;
 
+// Scratch of moe_spec_layer_step_static, the entry point for callers that cannot allocate device
+// memory: one array per GPU, held by every GPU the library runs on until the process ends.  Host code
+// never uses this name as an address: the device address is asked for once per device
+// (static_scratch_of_current_device) and handed to the kernels like any other pointer.
+static __device__ __align__(256) unsigned char scratch[MOE_SPEC_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each GPU, null until asked for
+
+// Device address of the scratch array on the current device (looked up once per device).
+hipError_t static_scratch_of_current_device(int *device, char **ptr) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = static_cast<char *>(p);
+  }
+  *device = dev;
+  *ptr = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 thread_local std::string g_create_error;
 
@@ -43,7 +73,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
+      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -80,24 +110,30 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
   a.slots = take(size_t(c->n_layers) * c->slots_per_layer * align_up(expert_bytes_of(c), 256));
+  // state that lives from call to call
+  a.counter = take((1 + kMaxBatch) * sizeof(unsigned int));
+  for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
+  a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
+  a.bench_ids = take(256);
+  a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
+  a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
+  a.dacc_end = off;
+  // scratch of one decode layer step: written before it is read within the call.  This is the part
+  // that moe_spec_layer_step_static keeps in the library's static array instead.
+  a.tr_begin = off;
   a.s_buf = take(B * H * 4);
   a.z = take(B * E * 8);
-  a.counter = take((1 + kMaxBatch) * sizeof(unsigned int));
   a.true_ids = take(B * k * 4);
   a.true_gates = take(B * k * 4);
   a.true_gates64 = take(B * k * 8);
-  for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
-  a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.h = take(B * k * I * 4);
   a.y = take(B * k * H * 4);
-  a.bench_ids = take(256);
   a.s_q = take(B * H * 2);
   a.sig = take(B * H * 4);
   a.est_u = take(B * size_t(c->est_latent) * 8);
   a.est_t = take(B * size_t(c->est_ffn) * 8);
   a.est_v = take(B * size_t(c->est_latent) * 8);
-  a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
-  a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
+  a.tr_end = off;
   const size_t P = size_t(c->max_prefill_tokens);
   a.pf_s = take(P * H * 4);
   a.pf_sq = take(P * H * 2);
@@ -118,6 +154,9 @@ struct moe_spec_ctx {
   size_t expert_bytes = 0, slot_stride = 0;
   ArenaLayout lay{};
   char *arena = nullptr;
+  int device = -1;                               // the device that was current at create
+  char *static_scratch = nullptr;                // this device's copy of the library's scratch array
+  bool use_static = false;                       // the running call keeps its step scratch there
   hipStream_t compute = nullptr, copy = nullptr;
   std::vector<hipStream_t> copy_aux;             // owned; further DMA queues of copy_engine 2
   std::vector<hipEvent_t> aux_done;
@@ -164,7 +203,13 @@ struct moe_spec_ctx {
     return fail(MOE_SPEC_EHIP, "%s: %s", what, hipGetErrorString(e));
   }
 
-  template <typename T> T *at(size_t off) const { return reinterpret_cast<T *>(arena + off); }
+  // Arena offset -> pointer.  The scratch of a decode layer step moves to the static array for a
+  // call of moe_spec_layer_step_static.
+  template <typename T> T *at(size_t off) const {
+    if (use_static && off >= lay.tr_begin && off < lay.tr_end)
+      return reinterpret_cast<T *>(static_scratch + (off - lay.tr_begin));
+    return reinterpret_cast<T *>(arena + off);
+  }
   char *pool_base(int layer) const {
     return arena + lay.slots + size_t(layer) * cfg.slots_per_layer * slot_stride;
   }
@@ -419,6 +464,8 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
     return MOE_SPEC_EHIP;
   };
   if ((e = init_kernels()) != hipSuccess) return bail(e, "kernel attributes");
+  if ((e = static_scratch_of_current_device(&c->device, &c->static_scratch)) != hipSuccess)
+    return bail(e, "address of the static scratch array");
   c->ready.assign(L, nullptr);
   c->done.assign(L, nullptr);
   for (int l = 0; l < L; ++l) {
@@ -454,7 +501,7 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   if ((e = hipMemsetAsync(c->arena + lay.counter, 0, (1 + kMaxBatch) * sizeof(unsigned int), c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
   if (cfg->accumulate_defaults) {
-    if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.pf_s - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
+    if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.dacc_end - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
   }
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return bail(e, "synchronize");
   *out = c;
@@ -565,9 +612,12 @@ int moe_spec_begin_token(moe_spec_ctx *c) {
   return MOE_SPEC_OK;
 }
 
-int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch, void *out_dev,
-                        const moe_spec_step_outputs *outs) {
-  if (!c) return MOE_SPEC_EINVAL;
+}  // extern "C"
+
+namespace {
+
+int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, void *out_dev,
+                    const moe_spec_step_outputs *outs) {
   const moe_spec_config &cfg = c->cfg;
   if (!r_dev || !out_dev) return c->fail(MOE_SPEC_EINVAL, "null activation pointer");
   if (batch < 1 || batch > cfg.max_batch) return c->fail(MOE_SPEC_EINVAL, "batch %d out of range", batch);
@@ -810,6 +860,35 @@ int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch
   if (last) c->token_open = false;
   c->st.layer_steps += 1;
   return MOE_SPEC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int moe_spec_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int batch, void *out_dev,
+                        const moe_spec_step_outputs *outs) {
+  if (!c) return MOE_SPEC_EINVAL;
+  c->use_static = false;
+  return layer_step_impl(c, layer, r_dev, batch, out_dev, outs);
+}
+
+int moe_spec_layer_step_static(moe_spec_ctx *c, int layer, const void *r_dev, int batch, void *out_dev,
+                               const moe_spec_step_outputs *outs) {
+  if (!c) return MOE_SPEC_EINVAL;
+  const size_t need = c->lay.tr_end - c->lay.tr_begin;
+  if (need > size_t(MOE_SPEC_STATIC_SCRATCH_BYTES))
+    return c->fail(MOE_SPEC_EINVAL, "this configuration needs %zu bytes of step scratch, the static array holds %zu: "
+                   "use moe_spec_layer_step (scratch in the arena) or a smaller max_batch", need,
+                   size_t(MOE_SPEC_STATIC_SCRATCH_BYTES));
+  if (c->cfg.profile) return c->fail(MOE_SPEC_ESTATE, "profile = 1 creates timing events; not available through the static entry point");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != c->device)
+    return c->fail(MOE_SPEC_ESTATE, "the current device is not the one the context was created on");
+  c->use_static = true;
+  const int rc = layer_step_impl(c, layer, r_dev, batch, out_dev, outs);
+  c->use_static = false;
+  return rc;
 }
 
 int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, int n_tokens, void *out_dev,
@@ -1055,7 +1134,7 @@ int moe_spec_reset(moe_spec_ctx *c) {
   if ((e = hipMemsetAsync(c->arena + c->lay.diag, 0, size_t(c->cfg.n_layers) * sizeof(LayerDiag), c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear counters");
   if (c->cfg.accumulate_defaults &&
-      (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.pf_s - c->lay.dacc_sum, c->compute)) != hipSuccess)
+      (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.dacc_end - c->lay.dacc_sum, c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear sums");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
   c->st = moe_spec_stats_t{};

@@ -86,7 +86,7 @@ class Engine:
         M.moe_spec_begin_token(self.ctx)
 
     def layer_step(self, layer: int, r: torch.Tensor, out: Optional[torch.Tensor] = None, want_ids=False,
-                   sync_input=True):
+                   sync_input=True, static_scratch=False):
         """r: [B,H] float32 on the device.  With sync_input the compute stream first waits for the
         caller's current torch stream (where r was produced); callers that already work on
         `self.compute` pass False."""
@@ -104,7 +104,8 @@ class Engine:
             outs = M.StepOutputs(**{k: v.data_ptr() for k, v in bufs.items()})
         if sync_input:
             self.compute.wait_stream(torch.cuda.current_stream(self.dev))
-        M.moe_spec_layer_step(self.ctx, layer, r.data_ptr(), B, out.data_ptr(), outs)
+        step = M.moe_spec_layer_step_static if static_scratch else M.moe_spec_layer_step
+        step(self.ctx, layer, r.data_ptr(), B, out.data_ptr(), outs)
         if sync_input:
             self._hand_back(r, out, *(bufs.values() if bufs else ()))
         return out, bufs

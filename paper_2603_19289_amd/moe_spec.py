@@ -14,6 +14,7 @@ OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 MODE_ON_DEMAND, MODE_SPECULATIVE, MODE_PREFETCH_HINT = 0, 1, 2
 F32, BF16 = 0, 1
 COPY_DMA, COPY_KERNEL, COPY_DMA2 = 0, 1, 2
+STATIC_SCRATCH_BYTES = 8 << 20
 
 
 class Config(C.Structure):
@@ -80,6 +81,7 @@ def lib():
         L.moe_spec_set_estimator_layers.argtypes = [vp, C.POINTER(C.c_uint8), i32]
         L.moe_spec_begin_token.argtypes = [vp]
         L.moe_spec_layer_step.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
+        L.moe_spec_layer_step_static.argtypes = [vp, i32, vp, i32, vp, C.POINTER(StepOutputs)]
         L.moe_spec_prefill_layer_step.argtypes = [vp, i32, vp, i32, vp, vp, vp]
         L.moe_spec_stats.argtypes = [vp, C.POINTER(Stats)]
         L.moe_spec_layer_diagnostics.argtypes = [vp, i32, C.POINTER(LayerDiag)]
@@ -138,6 +140,11 @@ def moe_spec_begin_token(ctx):
 def moe_spec_layer_step(ctx, layer, r_ptr, batch, out_ptr, outs: Optional[StepOutputs] = None):
     _check(lib().moe_spec_layer_step(ctx, layer, r_ptr, batch, out_ptr,
                                      C.byref(outs) if outs is not None else None), ctx)
+
+
+def moe_spec_layer_step_static(ctx, layer, r_ptr, batch, out_ptr, outs: Optional[StepOutputs] = None):
+    _check(lib().moe_spec_layer_step_static(ctx, layer, r_ptr, batch, out_ptr,
+                                            C.byref(outs) if outs is not None else None), ctx)
 
 
 def moe_spec_prefill_layer_step(ctx, layer, r_ptr, n_tokens, out_ptr, true_ids_ptr=None, true_gates_ptr=None):
