@@ -86,6 +86,9 @@ typedef struct {
                                        and disables the fused batch-1 down+combine kernel */
   int32_t max_prefill_tokens;       /* 0 <= P_max <= 32768: most prompt tokens one moe_spec_prefill_layer_step takes;
                                        0: no prefill path.  Costs about P_max*(k+2)*H floats of arena */
+  int32_t wait_spin_limit;          /* kernels that wait for another workgroup's result poll at most this
+                                       often before they give up and the call after reports MOE_SPEC_EHIP;
+                                       0: the default (about two seconds).  Tests force tiny values */
   int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
                                        feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
@@ -105,9 +108,11 @@ typedef struct {
                                        time, time the compute stream spent waiting for a copy */
   double  wall_ms;                  /* host clock from the first begin_token after create/reset to
                                        the end of this call's synchronisation */
-  double  gateup_ms;                /* profile=1 only: summed duration of the gate/up expert kernel
-                                       launches, each bracketed by two events on the compute stream */
-  int64_t gateup_launches;
+  double  expert_ms;                /* profile=1 only: summed duration of the expert FFN launches (one
+                                       launch at batch 1 where the fused kernel applies, else gate/up
+                                       and down), each cache wave bracketed by two events on the
+                                       compute stream */
+  int64_t expert_launches;          /* number of such brackets */
   int64_t prefill_tokens;           /* prompt tokens through moe_spec_prefill_layer_step, summed over layers */
 } moe_spec_stats_t;
 
@@ -243,7 +248,11 @@ const char *moe_spec_last_error(const moe_spec_ctx *ctx);
  * batch of one.  which: 0 = gate/up GEMV + SwiGLU, 1 = down GEMV + combine, 2 = router (true routing),
  * 3 = a kernel that only reads the gate/up bytes of the same slots (what streaming alone reaches),
  * 4 / 5 = the matrix-core gate/up / down kernels (bf16 only) on a batch of max_batch tokens whose
- * k*max_batch positions are dealt round-robin over min(S, E, k*max_batch) resident slots.
+ * k*max_batch positions are dealt round-robin over min(S, E, k*max_batch) resident slots,
+ * 6 = the fused routing kernel doing the true routing only, 7 = the same kernel doing the true routing and
+ * the prediction for the next layer (both routers and k default-vector rows), 8 = the fused batch-1 expert
+ * kernel (gate/up + SwiGLU + down + combine in one launch; MOE_SPEC_ESTATE where it does not apply),
+ * 9 = a kernel that only reads the W_down bytes of the same slots.
  * Writes the mean milliseconds per launch and the weight bytes one launch reads.
  * The slot contents are whatever the cache holds; outputs go to scratch.  Not inside a decode step. */
 int moe_spec_time_kernel(moe_spec_ctx *ctx, int which, int reps, double *ms_per_launch,

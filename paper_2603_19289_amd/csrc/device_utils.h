@@ -88,6 +88,16 @@ __device__ __forceinline__ double round_to_bf16(double x) {
   return ldexp(rint(m * 256.0), e - 8);
 }
 
+// The same rounding on the bits of the double: the 45 mantissa bits below bfloat16's seven are
+// rounded away to nearest, ties to even (a carry runs into the exponent as it should).  Finite
+// inputs whose magnitude is a normal float; zero stays zero.
+__device__ __forceinline__ double round_to_bf16_fast(double x) {
+  unsigned long long u = static_cast<unsigned long long>(__double_as_longlong(x));
+  u += 0x00000fffffffffffull + ((u >> 45) & 1ull);
+  u &= ~0x00001fffffffffffull;
+  return __longlong_as_double(static_cast<long long>(u));
+}
+
 // DPP controls used below: quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E,
 // row_half_mirror = 0x141, row_mirror = 0x140.  After the four steps every lane of a row of 16
 // holds the row's sum; one lane per row is then read through scalar registers.
@@ -121,6 +131,28 @@ __device__ __forceinline__ T wave_sum(T v) {
   v += dpp_move<0x141>(v);
   v += dpp_move<0x140>(v);
   return (readlane(v, 0) + readlane(v, 16)) + (readlane(v, 32) + readlane(v, 48));
+}
+
+// In-register rank sort of one token's logits.  Every wavefront holds all candidates in
+// registers (element i = r*64 + lane, R per lane) and counts, for each of its candidates, how
+// many candidates broadcast from source lanes [src_begin, src_end) rank before it: larger logit
+// first, equal logits by lower index.  The four wavefronts of the workgroup split the source
+// lanes and add their counts in LDS; a candidate's total is its position in the sorted order.
+template <int R>
+__device__ __forceinline__ void rank_counts(const double (&key)[R], int lane, int src_begin, int src_end,
+                                            int (&cnt)[R]) {
+#pragma unroll
+  for (int r = 0; r < R; ++r) cnt[r] = 0;
+  for (int j = src_begin; j < src_end; ++j) {
+#pragma unroll
+    for (int r2 = 0; r2 < R; ++r2) {
+      const double zj = readlane(key[r2], j);
+      const int ij = r2 * kWave + j;
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        cnt[r] += (zj > key[r] || (zj == key[r] && ij < r * kWave + lane)) ? 1 : 0;
+    }
+  }
 }
 
 }  // namespace moe_spec

@@ -581,11 +581,11 @@ __global__ __launch_bounds__(kBlock) void default_means_kernel(const double *sum
   mean[size_t(e) * H + i] = n ? float(sum[size_t(e) * H + i] / double(n)) : 0.f;
 }
 
-// Measurement aid: reads the gate/up matrices of the launch's slots and does nothing else (the
+// Measurement aid: reads a range of 16-byte units of the launch's slots and does nothing else (the
 // sum is never stored unless it hits an impossible value).  What a kernel can reach on these bytes.
-__global__ __launch_bounds__(kBlock) void stream_read_kernel(const ExpertArgs a, const ActiveList act, float *sink) {
-  const uint4 *p = reinterpret_cast<const uint4 *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes);
-  const size_t n16 = size_t(2) * a.I * a.H * (a.bf16 ? 2 : 4) / 16;
+__global__ __launch_bounds__(kBlock) void stream_read_kernel(const ExpertArgs a, const ActiveList act, size_t first16,
+                                                             size_t n16, float *sink) {
+  const uint4 *p = reinterpret_cast<const uint4 *>(a.pool + size_t(act.slot[blockIdx.y]) * a.slot_bytes) + first16;
   const size_t stride = size_t(gridDim.x) * kBlock;
   float acc = 0.f;
   for (size_t i = size_t(blockIdx.x) * kBlock + threadIdx.x; i < n16; i += stride) {
@@ -831,8 +831,8 @@ hipError_t launch_default_means(const double *sum, const unsigned long long *cnt
   return hipGetLastError();
 }
 
-hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, hipStream_t st) {
-  hipLaunchKernelGGL(stream_read_kernel, dim3(768, act.n), dim3(kBlock), 0, st, a, act, a.out);
+hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, size_t first16, size_t n16, hipStream_t st) {
+  hipLaunchKernelGGL(stream_read_kernel, dim3(768, act.n), dim3(kBlock), 0, st, a, act, first16, n16, a.out);
   return hipGetLastError();
 }
 

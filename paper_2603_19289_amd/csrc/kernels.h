@@ -66,6 +66,57 @@ struct RouteArgs {
   int bf16, spec, from_normalized, tok_tile;
 };
 
+// True routing of layer l and the prediction for layer l+1 in one launch (route_pair_kernel).  Logits
+// travel between the workgroups of a token through 8-byte slots that hold all ones until written; the
+// two sets of slots are used by alternate launches, and a launch re-arms the other set.
+struct RoutePairArgs {
+  const float *r;                         // [B,H] r_l
+  const void *w_true, *w_next;            // [E,H] routers of layers l and l+1; w_next null: no prediction
+  const float *gain_true, *gain_next;     // [H] gains of LN_l and LN_{l+1}
+  const void *dvec;                       // [E,H] default vectors d_{l,e}
+  unsigned long long *z_true, *z_pred;    // [B,E] logit slots of this launch, armed
+  unsigned long long *z_true_next, *z_pred_next;   // the other set, armed by this launch
+  int arm_count;                          // slots per set (largest batch * E)
+  float *s_out;                           // [B,H] s_l for the expert kernels
+  uint16_t *s_out_q;                      // [B,H] the same as bf16 bit patterns, or null
+  int32_t *true_ids;  float *true_gates;  // [B,k]
+  int32_t *next_ids;  float *next_gates;  // [B,k] the prediction carried to layer l+1
+  const int32_t *cmp_ids;                 // [B,k] prediction to score against this routing, or null
+  LayerDiag *diag;
+  int32_t *user_true_ids;  float *user_true_gates;   // optional copies for the caller
+  int32_t *user_next_ids;  float *user_next_gates;
+  Mailbox *mb_true, *mb_next;             // pinned host, or null
+  uint32_t seq_true, seq_next;
+  unsigned int *groups_done;              // [2] token groups that have reported (true, predicted); zero between launches
+  unsigned int *status;                   // raised when a bounded wait ran out
+  int B, H, E, k;
+  float eps;
+  int bf16, from_normalized;
+  unsigned int spin_limit;
+};
+bool route_pair_supported(int H, int dtype);
+hipError_t launch_route_pair(const RoutePairArgs &a, int dtype, hipStream_t st);
+
+// The expert FFN of a batch of one in one launch (expert_b1_kernel): gate/up workgroups hand the SwiGLU
+// products to the down-projection workgroups through 4-byte words that hold all ones until written.
+constexpr size_t kExpertB1MaxHqBytes = 48 << 10;
+struct ExpertB1Args {
+  const char *pool;           // first slot of the layer's pool
+  size_t slot_bytes;
+  int16_t slot[kMaxTopK];     // slot of the expert at each execution position
+  const float *s;             // [H] s_l
+  const float *gates;         // [k] mixing weights of the executed experts
+  uint32_t *hq, *hq_next;     // [k*I] SwiGLU products in the weight dtype, as 4-byte words: this launch's, armed; the other set, armed here
+  float *out;                 // [H]
+  int k, H, I, bf16;
+  int n_gateup_wg, gateup_wg_per_expert;   // filled by the launcher
+  float inv_chunks;
+  unsigned int spin_limit;
+  unsigned int *status;
+};
+bool expert_b1_fused_supported(int H, int I, int k, int dtype);
+hipError_t launch_expert_b1_fused(const ExpertB1Args &a, int dtype, hipStream_t st);
+
 // Expert kernels read weights from the device slots of one layer.
 struct ActiveList {           // experts executed by one launch and where they live
   int32_t n;
@@ -116,7 +167,8 @@ hipError_t launch_route(const RouteArgs &a, int dtype, hipStream_t st);
 hipError_t launch_gateup(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_down(const ExpertArgs &a, const ActiveList &act, int dtype, hipStream_t st);
 hipError_t launch_combine(const ExpertArgs &a, hipStream_t st);
-hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, hipStream_t st);
+// reads n16 16-byte units of every active slot, starting first16 units into the slot, and nothing else
+hipError_t launch_stream_read(const ExpertArgs &a, const ActiveList &act, size_t first16, size_t n16, hipStream_t st);
 hipError_t launch_gateup_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *s_q, uint16_t *hq,
                               hipStream_t st);
 hipError_t launch_down_mfma(const ExpertArgs &a, const ActiveList &act, const uint16_t *hq, hipStream_t st);

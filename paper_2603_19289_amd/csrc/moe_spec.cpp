@@ -69,11 +69,11 @@ struct Pool {                       // one layer's slot cache (least recently us
 
 constexpr int kDmaQueues = 2;        // copy_engine 2: the caller's copy stream plus one more
 
-struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 gate/up kernel
+struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 expert FFN of one cache wave
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
+      diag, zslots, hq2, fstate, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -96,6 +96,7 @@ const char *validate(const moe_spec_config *c) {
   if (c->est_latent < 0 || c->est_ffn < 0 || (c->est_latent == 0) != (c->est_ffn == 0)) return "estimator sizes must both be set or both be 0";
   if (c->est_latent % 8 || c->est_ffn % 8) return "estimator sizes must be multiples of 8";
   if (c->max_prefill_tokens < 0 || c->max_prefill_tokens > 32768) return "max_prefill_tokens out of range";
+  if (c->wait_spin_limit < 0) return "wait_spin_limit must be >= 0";
   if (c->est_latent > MOE_SPEC_MAX_HIDDEN || c->est_ffn > 8 * MOE_SPEC_MAX_HIDDEN) return "estimator sizes too large";
   return nullptr;
 }
@@ -115,6 +116,11 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
   a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.bench_ids = take(256);
+  // hand-over slots of the fused kernels: two sets each of true and predicted logits [B,E], two sets of
+  // SwiGLU products [k,I] as 4-byte words, all ones when armed; then the token-group counters (zero)
+  a.zslots = take(size_t(4) * B * E * 8);
+  a.hq2 = take(size_t(2) * k * I * 4);
+  a.fstate = take(256);
   a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
   a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
   a.dacc_end = off;
@@ -171,7 +177,11 @@ struct moe_spec_ctx {
   std::vector<char> done_recorded, ready_recorded;
   Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
   Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
+  volatile unsigned int *wait_status = nullptr;         // pinned host word after the mailboxes: a kernel's bounded wait ran out
+  unsigned int *wait_status_dev = nullptr;
+  unsigned int spin_limit = 1u << 21;
   uint32_t seq = 0;
+  uint32_t route_parity = 0, expert_parity = 0;         // which set of hand-over slots the next fused launch uses
 
   // token state
   bool token_open = false;
@@ -241,7 +251,7 @@ struct moe_spec_ctx {
         if (sp.kind == 0) st.compute_ms += ms;
         else if (sp.kind == 1) st.copy_ms += ms;
         else if (sp.kind == 2) st.stall_ms += ms;
-        else { st.gateup_ms += ms; st.gateup_launches += 1; }
+        else { st.expert_ms += ms; st.expert_launches += 1; }
       }
       free_events.push_back(sp.a);
       free_events.push_back(sp.b);
@@ -397,6 +407,26 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
 
+  // A waiter inside a fused kernel gave up: its results are not to be trusted, and the hand-over slots are
+  // in an unknown state until moe_spec_reset re-arms them.
+  int check_waits() {
+    if (wait_status && *wait_status)
+      return fail(MOE_SPEC_EHIP, "a kernel's bounded wait for another workgroup's result ran out; results since the "
+                  "last successful moe_spec_stats are invalid (moe_spec_reset re-arms the context)");
+    return MOE_SPEC_OK;
+  }
+  hipError_t arm_handover_slots() {
+    hipError_t e = hipMemsetAsync(arena + lay.zslots, 0xff, lay.fstate - lay.zslots, compute);
+    if (e == hipSuccess) e = hipMemsetAsync(arena + lay.fstate, 0, 256, compute);
+    route_parity = expert_parity = 0;
+    if (wait_status) *wait_status = 0;
+    return e;
+  }
+  unsigned long long *zslot_set(int which /*0 true, 1 predicted*/, uint32_t parity) const {
+    return at<unsigned long long>(lay.zslots) + (size_t(which) * 2 + parity) * cfg.max_batch * cfg.n_experts;
+  }
+  uint32_t *hq_set(uint32_t parity) const { return at<uint32_t>(lay.hq2) + size_t(parity) * cfg.top_k * cfg.inter; }
+
   static std::vector<int> sorted_union(const int32_t *ids, int n) {
     std::vector<int> u(ids, ids + n);
     std::sort(u.begin(), u.end());
@@ -488,15 +518,19 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   }
   void *mb = nullptr;
   // fine-grained (coherent) pinned memory: device stores become visible to the spinning host
-  if ((e = hipHostMalloc(&mb, 2 * sizeof(Mailbox), hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+  if ((e = hipHostMalloc(&mb, 2 * sizeof(Mailbox) + 64, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
     return bail(e, "pinned mailbox");
-  std::memset(mb, 0, 2 * sizeof(Mailbox));
+  std::memset(mb, 0, 2 * sizeof(Mailbox) + 64);
   c->mb_true = static_cast<Mailbox *>(mb);
   c->mb_next = c->mb_true + 1;
   void *mb_dev = nullptr;
   if ((e = hipHostGetDevicePointer(&mb_dev, mb, 0)) != hipSuccess) return bail(e, "mailbox device pointer");
   c->mb_true_dev = static_cast<Mailbox *>(mb_dev);
   c->mb_next_dev = c->mb_true_dev + 1;
+  c->wait_status = reinterpret_cast<volatile unsigned int *>(c->mb_true + 2);
+  c->wait_status_dev = reinterpret_cast<unsigned int *>(c->mb_true_dev + 2);
+  if (cfg->wait_spin_limit > 0) c->spin_limit = unsigned(cfg->wait_spin_limit);
+  if ((e = c->arm_handover_slots()) != hipSuccess) return bail(e, "arm hand-over slots");
   // counters start at zero
   if ((e = hipMemsetAsync(c->arena + lay.counter, 0, (1 + kMaxBatch) * sizeof(unsigned int), c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
@@ -637,8 +671,59 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
   hipError_t e;
 
+  if (int rc = c->check_waits()) return rc;
   TimedSpan *sp_route = c->open_span(0, c->compute);
 
+  const bool use_est = do_pred && c->est.set && !c->est_use.empty() && c->est_use[layer];
+  // One launch for the true routing and the prediction, unless the prediction comes from the estimator or
+  // from the baseline signal, or the per-layer figures' extra statistics are collected (those keep the
+  // one-kernel-per-routing path below).
+  const bool fused_route = !cfg.diagnostics && route_pair_supported(H, cfg.dtype) &&
+                           !(do_pred && (use_est || cfg.predict_signal == 1));
+  uint32_t ticket_next = 0;
+  const uint32_t ticket_true = ++c->seq;
+  if (fused_route) {
+    RoutePairArgs pa{};
+    pa.r = static_cast<const float *>(r_dev);
+    pa.w_true = c->router_w[layer];
+    pa.gain_true = static_cast<const float *>(c->gain[layer]);
+    if (do_pred) {
+      pa.w_next = c->router_w[layer + 1];
+      pa.gain_next = static_cast<const float *>(c->gain[layer + 1]);
+      pa.dvec = c->dvecs[layer];
+    }
+    pa.z_true = c->zslot_set(0, c->route_parity);
+    pa.z_pred = c->zslot_set(1, c->route_parity);
+    pa.z_true_next = c->zslot_set(0, c->route_parity ^ 1);
+    pa.z_pred_next = c->zslot_set(1, c->route_parity ^ 1);
+    pa.arm_count = cfg.max_batch * E;
+    c->route_parity ^= 1;
+    pa.s_out = c->at<float>(c->lay.s_buf);
+    pa.s_out_q = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch ? c->at<uint16_t>(c->lay.s_q) : nullptr;
+    pa.true_ids = c->at<int32_t>(c->lay.true_ids);
+    pa.true_gates = c->at<float>(c->lay.true_gates);
+    pa.next_ids = c->at<int32_t>(c->lay.pend_ids[(layer + 1) & 1]);
+    pa.next_gates = c->at<float>(c->lay.pend_gates[(layer + 1) & 1]);
+    pa.cmp_ids = c->have_pending ? c->at<int32_t>(c->lay.pend_ids[layer & 1]) : nullptr;
+    pa.diag = c->at<LayerDiag>(c->lay.diag) + layer;
+    if (outs) {
+      pa.user_true_ids = outs->true_ids; pa.user_true_gates = outs->true_gates;
+      pa.user_next_ids = outs->next_ids; pa.user_next_gates = outs->next_gates;
+    }
+    pa.mb_true = exec_pred ? nullptr : c->mb_true_dev;
+    pa.seq_true = ticket_true;
+    if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; ticket_next = ++c->seq; pa.seq_next = ticket_next; }
+    pa.groups_done = c->at<unsigned int>(c->lay.fstate);
+    pa.status = c->wait_status_dev;
+    pa.B = batch; pa.H = H; pa.E = E; pa.k = k;
+    pa.eps = cfg.rms_eps;
+    pa.bf16 = cfg.dtype == MOE_SPEC_BF16;
+    pa.from_normalized = cfg.q_from_normalized;
+    pa.spin_limit = c->spin_limit;
+    if ((e = launch_route_pair(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+    c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
+    if (do_pred) c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+  } else {
   // --- true routing of layer l (and scoring of the prediction made at l-1)
   RouteArgs ra{};
   ra.r = static_cast<const float *>(r_dev);
@@ -658,7 +743,6 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   ra.user_ids = outs ? outs->true_ids : nullptr;
   ra.user_gates = outs ? outs->true_gates : nullptr;
   ra.mailbox = exec_pred ? nullptr : c->mb_true_dev;
-  const uint32_t ticket_true = ++c->seq;
   ra.seq = ticket_true;
   ra.B = batch; ra.H = H; ra.E = E; ra.k = k;
   ra.eps = cfg.rms_eps;
@@ -668,7 +752,6 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
 
   // --- prediction for layer l+1 from the quasi-hidden state
-  uint32_t ticket_next = 0;
   if (do_pred) {
     RouteArgs pa = ra;
     pa.s_in = c->at<float>(c->lay.s_buf);
@@ -691,7 +774,6 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     pa.seq = ticket_next;
     pa.spec = cfg.predict_signal == 1 ? 2 : 1;
     pa.from_normalized = cfg.q_from_normalized;
-    const bool use_est = c->est.set && !c->est_use.empty() && c->est_use[layer];
     if (use_est) {
       // The routing launch only produces the predicting signal; the estimator's four steps turn it
       // into logits, and its last step (the routing kernel in LayerNorm mode) selects and hands over.
@@ -736,6 +818,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
     }
   }
+  }   // one kernel per routing
   c->close_span(sp_route, c->compute);
 
   // --- which experts run, and where their ids and gates live on the device
@@ -801,7 +884,24 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       return c->hip_fail(e, "compute stream wait");
     if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
     TimedSpan *sp_gu = c->open_span(3, c->compute);
-    if (fast_b1) {
+    if (fast_b1 && expert_b1_fused_supported(H, I, k, cfg.dtype)) {
+      // the whole FFN of the token in one launch
+      ExpertB1Args fa{};
+      fa.pool = xa.pool;
+      fa.slot_bytes = xa.slot_bytes;
+      for (int j = 0; j < k; ++j) fa.slot[j] = int16_t(c->pools[layer].where[exec_ids_host[j]]);
+      fa.s = xa.s;
+      fa.gates = exec_gates_dev;
+      fa.hq = c->hq_set(c->expert_parity);
+      fa.hq_next = c->hq_set(c->expert_parity ^ 1);
+      c->expert_parity ^= 1;
+      fa.out = xa.out;
+      fa.k = k; fa.H = H; fa.I = I; fa.bf16 = xa.bf16;
+      fa.spin_limit = c->spin_limit;
+      fa.status = c->wait_status_dev;
+      if ((e = launch_expert_b1_fused(fa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "expert kernel");
+      c->close_span(sp_gu, c->compute);
+    } else if (fast_b1) {
       // batch 1: the k executed experts are one wave; hand the kernels the slots in position order
       ActiveList by_pos{};
       by_pos.n = k;
@@ -810,18 +910,18 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
         by_pos.slot[j] = int16_t(c->pools[layer].where[exec_ids_host[j]]);
       }
       if ((e = launch_gateup_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
-      c->close_span(sp_gu, c->compute);
       if ((e = launch_down_combine_b1(xa, by_pos, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+      c->close_span(sp_gu, c->compute);
     } else if (use_mfma) {
       uint16_t *hq = c->at<uint16_t>(c->lay.h);
       if ((e = launch_gateup_mfma(xa, act, c->at<uint16_t>(c->lay.s_q), hq, c->compute)) != hipSuccess)
         return c->hip_fail(e, "gate/up MFMA kernel");
-      c->close_span(sp_gu, c->compute);
       if ((e = launch_down_mfma(xa, act, hq, c->compute)) != hipSuccess) return c->hip_fail(e, "down MFMA kernel");
+      c->close_span(sp_gu, c->compute);
     } else {
       if ((e = launch_gateup(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "gate/up kernel");
-      c->close_span(sp_gu, c->compute);
       if ((e = launch_down(xa, act, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "down kernel");
+      c->close_span(sp_gu, c->compute);
     }
     if (cfg.accumulate_defaults &&
         (e = launch_accumulate_defaults(xa, act, c->at<double>(c->lay.dacc_sum) + size_t(layer) * E * H,
@@ -1070,6 +1170,7 @@ int moe_spec_stats(moe_spec_ctx *c, moe_spec_stats_t *out) {
   if (e != hipSuccess) return c->hip_fail(e, "synchronize");
   int rc = c->resolve_spans();
   if (rc) return rc;
+  if ((rc = c->check_waits())) return rc;
   std::vector<LayerDiag> dg(c->cfg.n_layers);
   if ((e = hipMemcpy(dg.data(), c->arena + c->lay.diag, dg.size() * sizeof(LayerDiag), hipMemcpyDeviceToHost)) != hipSuccess)
     return c->hip_fail(e, "read hit counters");
@@ -1136,6 +1237,7 @@ int moe_spec_reset(moe_spec_ctx *c) {
   if (c->cfg.accumulate_defaults &&
       (e = hipMemsetAsync(c->arena + c->lay.dacc_sum, 0, c->lay.dacc_end - c->lay.dacc_sum, c->compute)) != hipSuccess)
     return c->hip_fail(e, "clear sums");
+  if ((e = c->arm_handover_slots()) != hipSuccess) return c->hip_fail(e, "arm hand-over slots");
   if ((e = hipStreamSynchronize(c->compute)) != hipSuccess) return c->hip_fail(e, "synchronize");
   c->st = moe_spec_stats_t{};
   c->clock_running = false;
@@ -1148,14 +1250,18 @@ int moe_spec_reset(moe_spec_ctx *c) {
 
 int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_launch, int64_t *bytes_per_launch) {
   if (!c) return MOE_SPEC_EINVAL;
-  if (which < 0 || which > 5 || reps < 1 || !ms_per_launch || !bytes_per_launch)
+  if (which < 0 || which > 9 || reps < 1 || !ms_per_launch || !bytes_per_launch)
     return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
   if (which >= 4 && c->cfg.dtype != MOE_SPEC_BF16) return c->fail(MOE_SPEC_ESTATE, "the matrix-core kernels need bf16 weights");
   if (c->token_open) return c->fail(MOE_SPEC_ESTATE, "time_kernel inside a decode step");
   const moe_spec_config &cfg = c->cfg;
   const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter;
   const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
-  if (which == 2) for (int l = 0; l < L; ++l) if (!c->router_w[l]) return c->fail(MOE_SPEC_ESTATE, "resident tables not set");
+  if ((which == 6 || which == 7) && (!c->router_w[0] || !route_pair_supported(H, cfg.dtype)))
+    return c->fail(MOE_SPEC_ESTATE, "the fused routing kernel does not apply to this configuration");
+  if (which == 8 && !expert_b1_fused_supported(H, I, k, cfg.dtype))
+    return c->fail(MOE_SPEC_ESTATE, "the fused batch-1 expert kernel does not apply to this configuration");
+  if (which == 2 || which == 6 || which == 7) for (int l = 0; l < L; ++l) if (!c->router_w[l]) return c->fail(MOE_SPEC_ESTATE, "resident tables not set");
   hipError_t e;
   int32_t ids[kMaxTopK];
   ActiveList act{};
@@ -1212,7 +1318,53 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
       xa.pool = c->pool_base(l);
       if (which == 0) le = fast ? launch_gateup_b1(xa, act, cfg.dtype, c->compute) : launch_gateup(xa, act, cfg.dtype, c->compute);
       else if (which == 1) le = fast ? launch_down_combine_b1(xa, act, cfg.dtype, c->compute) : launch_down(xa, act, cfg.dtype, c->compute);
-      else if (which == 3) le = launch_stream_read(xa, act, c->compute);
+      else if (which == 3) le = launch_stream_read(xa, act, 0, size_t(2) * I * H * wbytes / 16, c->compute);
+      else if (which == 9) le = launch_stream_read(xa, act, size_t(2) * I * H * wbytes / 16, size_t(I) * H * wbytes / 16, c->compute);
+      else if (which == 6 || which == 7) {
+        RoutePairArgs pa{};
+        pa.r = c->at<float>(c->lay.s_buf);
+        pa.w_true = c->router_w[l];
+        pa.gain_true = static_cast<const float *>(c->gain[l]);
+        if (which == 7) {
+          pa.w_next = c->router_w[(l + 1) % L];
+          pa.gain_next = static_cast<const float *>(c->gain[(l + 1) % L]);
+          pa.dvec = c->dvecs[l];
+        }
+        pa.z_true = c->zslot_set(0, c->route_parity);
+        pa.z_pred = c->zslot_set(1, c->route_parity);
+        pa.z_true_next = c->zslot_set(0, c->route_parity ^ 1);
+        pa.z_pred_next = c->zslot_set(1, c->route_parity ^ 1);
+        pa.arm_count = cfg.max_batch * E;
+        c->route_parity ^= 1;
+        pa.s_out = c->at<float>(c->lay.sig);
+        pa.true_ids = c->at<int32_t>(c->lay.true_ids);
+        pa.true_gates = c->at<float>(c->lay.true_gates);
+        pa.next_ids = c->at<int32_t>(c->lay.bench_ids) + 32;
+        pa.next_gates = c->at<float>(c->lay.bench_ids) + 48;
+        pa.diag = c->at<LayerDiag>(c->lay.diag);
+        pa.groups_done = c->at<unsigned int>(c->lay.fstate);
+        pa.status = c->wait_status_dev;
+        pa.B = 1; pa.H = H; pa.E = E; pa.k = k;
+        pa.eps = cfg.rms_eps;
+        pa.bf16 = xa.bf16;
+        pa.spin_limit = c->spin_limit;
+        le = launch_route_pair(pa, cfg.dtype, c->compute);
+      } else if (which == 8) {
+        ExpertB1Args fa{};
+        fa.pool = xa.pool;
+        fa.slot_bytes = xa.slot_bytes;
+        for (int j = 0; j < k; ++j) fa.slot[j] = int16_t(j);
+        fa.s = xa.s;
+        fa.gates = xa.exec_gates;
+        fa.hq = c->hq_set(c->expert_parity);
+        fa.hq_next = c->hq_set(c->expert_parity ^ 1);
+        c->expert_parity ^= 1;
+        fa.out = xa.out;
+        fa.k = k; fa.H = H; fa.I = I; fa.bf16 = xa.bf16;
+        fa.spin_limit = c->spin_limit;
+        fa.status = c->wait_status_dev;
+        le = launch_expert_b1_fused(fa, cfg.dtype, c->compute);
+      }
       else if (which == 4) { xm.pool = xa.pool; le = launch_gateup_mfma(xm, act_m, c->at<uint16_t>(c->lay.s_q), c->at<uint16_t>(c->lay.h), c->compute); }
       else if (which == 5) { xm.pool = xa.pool; le = launch_down_mfma(xm, act_m, c->at<uint16_t>(c->lay.h), c->compute); }
       else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
@@ -1228,7 +1380,9 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   if (e != hipSuccess) return c->hip_fail(e, "timing");
   *ms_per_launch = double(ms) / reps;
   *bytes_per_launch = which == 0 || which == 3 ? int64_t(k) * 2 * I * H * wbytes
-                    : which == 1 ? int64_t(k) * I * H * wbytes
+                    : which == 1 || which == 9 ? int64_t(k) * I * H * wbytes
+                    : which == 7 ? 2 * int64_t(E) * H * wbytes + int64_t(k) * H * wbytes
+                    : which == 8 ? int64_t(k) * 3 * I * H * wbytes
                     : which == 4 ? int64_t(n_act) * 2 * I * H * wbytes
                     : which == 5 ? int64_t(n_act) * I * H * wbytes
                                  : int64_t(E) * H * wbytes;

@@ -39,28 +39,6 @@ __device__ __forceinline__ double load_coherent(const double *p) {
   return __longlong_as_double(static_cast<long long>(u));
 }
 
-// In-register rank sort of one token's logits.  Every wavefront holds all candidates in
-// registers (element i = r*64 + lane, R per lane) and counts, for each of its candidates, how
-// many candidates broadcast from source lanes [src_begin, src_end) rank before it: larger logit
-// first, equal logits by lower index.  The four wavefronts of the workgroup split the source
-// lanes and add their counts in LDS; a candidate's total is its position in the sorted order.
-template <int R>
-__device__ __forceinline__ void rank_counts(const double (&key)[R], int lane, int src_begin, int src_end,
-                                            int (&cnt)[R]) {
-#pragma unroll
-  for (int r = 0; r < R; ++r) cnt[r] = 0;
-  for (int j = src_begin; j < src_end; ++j) {
-#pragma unroll
-    for (int r2 = 0; r2 < R; ++r2) {
-      const double zj = readlane(key[r2], j);
-      const int ij = r2 * kWave + j;
-#pragma unroll
-      for (int r = 0; r < R; ++r)
-        cnt[r] += (zj > key[r] || (zj == key[r] && ij < r * kWave + lane)) ? 1 : 0;
-    }
-  }
-}
-
 struct FinishShared {
   int rank[kMaxExperts];
   double top_z[kMaxTopK];

@@ -230,12 +230,14 @@ def test_time_kernel_modes_and_their_byte_counts():
     w = 2
     want = {0: wl.top_k * 2 * wl.inter * wl.hidden * w, 1: wl.top_k * wl.inter * wl.hidden * w,
             2: wl.n_experts * wl.hidden * w, 3: wl.top_k * 2 * wl.inter * wl.hidden * w,
-            4: 5 * 2 * wl.inter * wl.hidden * w, 5: 5 * wl.inter * wl.hidden * w}     # 5 = min(S, E, B*k) slots
+            4: 5 * 2 * wl.inter * wl.hidden * w, 5: 5 * wl.inter * wl.hidden * w,     # 5 = min(S, E, B*k) slots
+            6: wl.n_experts * wl.hidden * w, 7: (2 * wl.n_experts + wl.top_k) * wl.hidden * w,
+            8: wl.top_k * 3 * wl.inter * wl.hidden * w, 9: wl.top_k * wl.inter * wl.hidden * w}
     for which, nbytes in want.items():
         ms, got = eng.time_kernel(which, 6)
         assert ms > 0 and got == nbytes, (which, ms, got, nbytes)
     with pytest.raises(M.MoeSpecError):
-        eng.time_kernel(6, 1)
+        eng.time_kernel(10, 1)
     eng.begin_token()
     with pytest.raises(M.MoeSpecError) as ei:
         eng.time_kernel(0, 1)                    # not inside a decode step
@@ -285,3 +287,52 @@ def test_non_finite_inputs_keep_expert_ids_in_range(dtype, B):
                 np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), want.exec_ids)
         finally:
             eng.close()
+
+
+def test_a_wait_that_runs_out_is_reported_and_reset_recovers():
+    # The fused kernels wait, boundedly, for results of other workgroups of the same launch.  With the bound
+    # forced down to one poll from the host, waiters give up early: every kernel still runs to its end, ids
+    # stay inside [0, E), the next call (or moe_spec_stats) reports the failure, and moe_spec_reset brings
+    # the context back.  With the default bound the same inputs match the checker.
+    wl = small_workload(n_layers=3, hidden=512, n_experts=64, top_k=4, inter=256, dtype="bf16", slots=8, tokens=3, seed=77)
+    res, ex, model = build(wl, "random")
+    x0, eps = W.make_inputs(wl)
+    orc = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
+    trace = O.run_tokens(orc, x0, make_advance(wl, eps))
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex, wait_spin_limit=1)
+    gave_up = False
+    try:
+        for t in range(wl.tokens):
+            try:
+                eng.begin_token()
+                for l in range(wl.n_layers):
+                    _, ids = eng.layer_step(l, torch.from_numpy(trace[t][l][0].astype(np.float32)).cuda(), want_ids=True)
+                    torch.cuda.synchronize()
+                    got = ids["exec_ids"].cpu().numpy()
+                    assert ((got >= 0) & (got < wl.n_experts)).all()
+            except M.MoeSpecError as err:
+                assert err.code == M.EHIP and "bounded wait" in str(err)
+                gave_up = True
+                break
+        if not gave_up:
+            try:
+                eng.stats()
+            except M.MoeSpecError as err:
+                assert err.code == M.EHIP and "bounded wait" in str(err)
+                gave_up = True
+        print(f"[bounded wait] one poll allowed: waiters gave up = {gave_up}", flush=True)
+        eng.reset()
+        assert eng.stats()["tokens"] == 0                        # the context answers again
+    finally:
+        eng.close()
+    eng = _engine(wl, M.MODE_SPECULATIVE, res, ex)
+    try:
+        for t in range(wl.tokens):
+            eng.begin_token()
+            for l in range(wl.n_layers):
+                _, ids = eng.layer_step(l, torch.from_numpy(trace[t][l][0].astype(np.float32)).cuda(), want_ids=True)
+                torch.cuda.synchronize()
+                np.testing.assert_array_equal(ids["exec_ids"].cpu().numpy(), trace[t][l][1].exec_ids)
+        assert eng.stats()["hits"] == orc.stats.hits
+    finally:
+        eng.close()
