@@ -108,8 +108,7 @@ typedef struct {
                                        time, time the compute stream spent waiting for a copy */
   double  wall_ms;                  /* host clock from the first begin_token after create/reset to
                                        the end of this call's synchronisation */
-  double  expert_ms;                /* profile=1 only: summed duration of the expert FFN launches (one
-                                       launch at batch 1 where the fused kernel applies, else gate/up
+  double  expert_ms;                /* profile=1 only: summed duration of the expert FFN launches (gate/up
                                        and down), each cache wave bracketed by two events on the
                                        compute stream */
   int64_t expert_launches;          /* number of such brackets */
@@ -250,9 +249,9 @@ const char *moe_spec_last_error(const moe_spec_ctx *ctx);
  * 4 / 5 = the matrix-core gate/up / down kernels (bf16 only) on a batch of max_batch tokens whose
  * k*max_batch positions are dealt round-robin over min(S, E, k*max_batch) resident slots,
  * 6 = the fused routing kernel doing the true routing only, 7 = the same kernel doing the true routing and
- * the prediction for the next layer (both routers and k default-vector rows), 8 = the fused batch-1 expert
- * kernel (gate/up + SwiGLU + down + combine in one launch; MOE_SPEC_ESTATE where it does not apply),
- * 9 = a kernel that only reads the W_down bytes of the same slots.
+ * the prediction for the next layer (both routers and k default-vector rows per token), both on a batch of
+ * max_batch tokens,
+ * 9 = a kernel that only reads the W_down bytes of the same slots (8 is not used).
  * Writes the mean milliseconds per launch and the weight bytes one launch reads.
  * The slot contents are whatever the cache holds; outputs go to scratch.  Not inside a decode step. */
 int moe_spec_time_kernel(moe_spec_ctx *ctx, int which, int reps, double *ms_per_launch,

@@ -85,37 +85,16 @@ struct RoutePairArgs {
   LayerDiag *diag;
   int32_t *user_true_ids;  float *user_true_gates;   // optional copies for the caller
   int32_t *user_next_ids;  float *user_next_gates;
-  Mailbox *mb_true, *mb_next;             // pinned host, or null
-  uint32_t seq_true, seq_next;
-  unsigned int *groups_done;              // [2] token groups that have reported (true, predicted); zero between launches
+  Mailbox *mb_true, *mb_next;             // pinned host, or null: ids[B*k] words the host set to -1 and waits for
   unsigned int *status;                   // raised when a bounded wait ran out
   int B, H, E, k;
   float eps;
   int bf16, from_normalized;
   unsigned int spin_limit;
+  unsigned long long *stage_clock;        // development builds only (MOE_SPEC_STAGE_CLOCK): [12] stage times, or null
 };
 bool route_pair_supported(int H, int dtype);
 hipError_t launch_route_pair(const RoutePairArgs &a, int dtype, hipStream_t st);
-
-// The expert FFN of a batch of one in one launch (expert_b1_kernel): gate/up workgroups hand the SwiGLU
-// products to the down-projection workgroups through 4-byte words that hold all ones until written.
-constexpr size_t kExpertB1MaxHqBytes = 48 << 10;
-struct ExpertB1Args {
-  const char *pool;           // first slot of the layer's pool
-  size_t slot_bytes;
-  int16_t slot[kMaxTopK];     // slot of the expert at each execution position
-  const float *s;             // [H] s_l
-  const float *gates;         // [k] mixing weights of the executed experts
-  uint32_t *hq, *hq_next;     // [k*I] SwiGLU products in the weight dtype, as 4-byte words: this launch's, armed; the other set, armed here
-  float *out;                 // [H]
-  int k, H, I, bf16;
-  int n_gateup_wg, gateup_wg_per_expert;   // filled by the launcher
-  float inv_chunks;
-  unsigned int spin_limit;
-  unsigned int *status;
-};
-bool expert_b1_fused_supported(int H, int I, int k, int dtype);
-hipError_t launch_expert_b1_fused(const ExpertB1Args &a, int dtype, hipStream_t st);
 
 // Expert kernels read weights from the device slots of one layer.
 struct ActiveList {           // experts executed by one launch and where they live

@@ -73,7 +73,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, zslots, hq2, fstate, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
+      diag, zslots, fstate, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -116,10 +116,9 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
   a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.bench_ids = take(256);
-  // hand-over slots of the fused kernels: two sets each of true and predicted logits [B,E], two sets of
-  // SwiGLU products [k,I] as 4-byte words, all ones when armed; then the token-group counters (zero)
+  // hand-over slots of the fused routing kernel: two sets each of true and predicted logits [B,E], all
+  // ones when armed; then the token-group counters (zero)
   a.zslots = take(size_t(4) * B * E * 8);
-  a.hq2 = take(size_t(2) * k * I * 4);
   a.fstate = take(256);
   a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
   a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
@@ -181,7 +180,7 @@ struct moe_spec_ctx {
   unsigned int *wait_status_dev = nullptr;
   unsigned int spin_limit = 1u << 21;
   uint32_t seq = 0;
-  uint32_t route_parity = 0, expert_parity = 0;         // which set of hand-over slots the next fused launch uses
+  uint32_t route_parity = 0;                            // which set of logit slots the next fused routing launch uses
 
   // token state
   bool token_open = false;
@@ -274,6 +273,28 @@ struct moe_spec_ctx {
           return fail(MOE_SPEC_EHIP, "routing kernel finished without posting expert ids");
         if (std::chrono::steady_clock::now() - start > std::chrono::seconds(30))
           return fail(MOE_SPEC_EHIP, "timed out waiting for expert ids from the routing kernel");
+      }
+    }
+    __atomic_thread_fence(__ATOMIC_ACQUIRE);
+    return MOE_SPEC_OK;
+  }
+
+  // The fused routing kernel overwrites id words that the host armed with -1: spin until all n are there.
+  int wait_ids(const Mailbox *mb, int n) {
+    const volatile int32_t *ids = mb->ids;
+    auto start = std::chrono::steady_clock::now();
+    unsigned long spins = 0;
+    for (int i = 0; i < n; ++i) {
+      while (ids[i] == -1) {
+        __builtin_ia32_pause();
+        if ((++spins & 0xfffff) == 0) {
+          hipError_t q = hipStreamQuery(compute);
+          if (q != hipSuccess && q != hipErrorNotReady) return hip_fail(q, "compute stream failed while routing");
+          if (q == hipSuccess && ids[i] == -1)
+            return fail(MOE_SPEC_EHIP, "routing kernel finished without posting expert ids");
+          if (std::chrono::steady_clock::now() - start > std::chrono::seconds(30))
+            return fail(MOE_SPEC_EHIP, "timed out waiting for expert ids from the routing kernel");
+        }
       }
     }
     __atomic_thread_fence(__ATOMIC_ACQUIRE);
@@ -418,14 +439,13 @@ struct moe_spec_ctx {
   hipError_t arm_handover_slots() {
     hipError_t e = hipMemsetAsync(arena + lay.zslots, 0xff, lay.fstate - lay.zslots, compute);
     if (e == hipSuccess) e = hipMemsetAsync(arena + lay.fstate, 0, 256, compute);
-    route_parity = expert_parity = 0;
+    route_parity = 0;
     if (wait_status) *wait_status = 0;
     return e;
   }
   unsigned long long *zslot_set(int which /*0 true, 1 predicted*/, uint32_t parity) const {
     return at<unsigned long long>(lay.zslots) + (size_t(which) * 2 + parity) * cfg.max_batch * cfg.n_experts;
   }
-  uint32_t *hq_set(uint32_t parity) const { return at<uint32_t>(lay.hq2) + size_t(parity) * cfg.top_k * cfg.inter; }
 
   static std::vector<int> sorted_union(const int32_t *ids, int n) {
     std::vector<int> u(ids, ids + n);
@@ -710,10 +730,10 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       pa.user_true_ids = outs->true_ids; pa.user_true_gates = outs->true_gates;
       pa.user_next_ids = outs->next_ids; pa.user_next_gates = outs->next_gates;
     }
-    pa.mb_true = exec_pred ? nullptr : c->mb_true_dev;
-    pa.seq_true = ticket_true;
-    if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; ticket_next = ++c->seq; pa.seq_next = ticket_next; }
-    pa.groups_done = c->at<unsigned int>(c->lay.fstate);
+    // the host arms the id words it will wait for; the kernel's workgroups overwrite them
+    if (!exec_pred) { pa.mb_true = c->mb_true_dev; std::memset(c->mb_true->ids, 0xff, size_t(batch) * k * 4); }
+    if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; std::memset(c->mb_next->ids, 0xff, size_t(batch) * k * 4); }
+    __atomic_thread_fence(__ATOMIC_RELEASE);
     pa.status = c->wait_status_dev;
     pa.B = batch; pa.H = H; pa.E = E; pa.k = k;
     pa.eps = cfg.rms_eps;
@@ -831,7 +851,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     exec_ids_dev = c->at<int32_t>(c->lay.pend_ids[layer & 1]);
     exec_gates_dev = c->at<float>(c->lay.pend_gates[layer & 1]);
   } else {
-    int rc = c->wait_mailbox(c->mb_true, ticket_true);
+    int rc = fused_route ? c->wait_ids(c->mb_true, batch * k) : c->wait_mailbox(c->mb_true, ticket_true);
     if (rc) return rc;
     if ((rc = c->check_ids(c->mb_true->ids, batch * k))) return rc;
     exec_union = moe_spec_ctx::sorted_union(c->mb_true->ids, batch * k);
@@ -884,24 +904,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       return c->hip_fail(e, "compute stream wait");
     if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
     TimedSpan *sp_gu = c->open_span(3, c->compute);
-    if (fast_b1 && expert_b1_fused_supported(H, I, k, cfg.dtype)) {
-      // the whole FFN of the token in one launch
-      ExpertB1Args fa{};
-      fa.pool = xa.pool;
-      fa.slot_bytes = xa.slot_bytes;
-      for (int j = 0; j < k; ++j) fa.slot[j] = int16_t(c->pools[layer].where[exec_ids_host[j]]);
-      fa.s = xa.s;
-      fa.gates = exec_gates_dev;
-      fa.hq = c->hq_set(c->expert_parity);
-      fa.hq_next = c->hq_set(c->expert_parity ^ 1);
-      c->expert_parity ^= 1;
-      fa.out = xa.out;
-      fa.k = k; fa.H = H; fa.I = I; fa.bf16 = xa.bf16;
-      fa.spin_limit = c->spin_limit;
-      fa.status = c->wait_status_dev;
-      if ((e = launch_expert_b1_fused(fa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "expert kernel");
-      c->close_span(sp_gu, c->compute);
-    } else if (fast_b1) {
+    if (fast_b1) {
       // batch 1: the k executed experts are one wave; hand the kernels the slots in position order
       ActiveList by_pos{};
       by_pos.n = k;
@@ -938,7 +941,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   // --- prefetch the first wave of the predicted experts of layer l+1
   c->have_pending = do_pred;
   if (do_pred && prefetching) {
-    int rc = c->wait_mailbox(c->mb_next, ticket_next);
+    int rc = fused_route ? c->wait_ids(c->mb_next, batch * k) : c->wait_mailbox(c->mb_next, ticket_next);
     if (rc) return rc;
     if ((rc = c->check_ids(c->mb_next->ids, batch * k))) return rc;
     c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
@@ -1250,7 +1253,7 @@ int moe_spec_reset(moe_spec_ctx *c) {
 
 int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_launch, int64_t *bytes_per_launch) {
   if (!c) return MOE_SPEC_EINVAL;
-  if (which < 0 || which > 9 || reps < 1 || !ms_per_launch || !bytes_per_launch)
+  if (which < 0 || which > 9 || which == 8 || reps < 1 || !ms_per_launch || !bytes_per_launch)
     return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
   if (which >= 4 && c->cfg.dtype != MOE_SPEC_BF16) return c->fail(MOE_SPEC_ESTATE, "the matrix-core kernels need bf16 weights");
   if (c->token_open) return c->fail(MOE_SPEC_ESTATE, "time_kernel inside a decode step");
@@ -1259,8 +1262,6 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   const size_t wbytes = cfg.dtype == MOE_SPEC_BF16 ? 2 : 4;
   if ((which == 6 || which == 7) && (!c->router_w[0] || !route_pair_supported(H, cfg.dtype)))
     return c->fail(MOE_SPEC_ESTATE, "the fused routing kernel does not apply to this configuration");
-  if (which == 8 && !expert_b1_fused_supported(H, I, k, cfg.dtype))
-    return c->fail(MOE_SPEC_ESTATE, "the fused batch-1 expert kernel does not apply to this configuration");
   if (which == 2 || which == 6 || which == 7) for (int l = 0; l < L; ++l) if (!c->router_w[l]) return c->fail(MOE_SPEC_ESTATE, "resident tables not set");
   hipError_t e;
   int32_t ids[kMaxTopK];
@@ -1339,31 +1340,19 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
         pa.s_out = c->at<float>(c->lay.sig);
         pa.true_ids = c->at<int32_t>(c->lay.true_ids);
         pa.true_gates = c->at<float>(c->lay.true_gates);
-        pa.next_ids = c->at<int32_t>(c->lay.bench_ids) + 32;
-        pa.next_gates = c->at<float>(c->lay.bench_ids) + 48;
+        pa.next_ids = c->at<int32_t>(c->lay.pend_ids[0]);
+        pa.next_gates = c->at<float>(c->lay.pend_gates[0]);
         pa.diag = c->at<LayerDiag>(c->lay.diag);
-        pa.groups_done = c->at<unsigned int>(c->lay.fstate);
         pa.status = c->wait_status_dev;
-        pa.B = 1; pa.H = H; pa.E = E; pa.k = k;
+        pa.B = Bm; pa.H = H; pa.E = E; pa.k = k;
         pa.eps = cfg.rms_eps;
         pa.bf16 = xa.bf16;
         pa.spin_limit = c->spin_limit;
+#ifdef MOE_SPEC_STAGE_CLOCK
+        pa.mb_true = c->mb_true_dev; pa.mb_next = c->mb_next_dev;     // as in a prefetching decode step
+        pa.stage_clock = c->at<unsigned long long>(c->lay.y);
+#endif
         le = launch_route_pair(pa, cfg.dtype, c->compute);
-      } else if (which == 8) {
-        ExpertB1Args fa{};
-        fa.pool = xa.pool;
-        fa.slot_bytes = xa.slot_bytes;
-        for (int j = 0; j < k; ++j) fa.slot[j] = int16_t(j);
-        fa.s = xa.s;
-        fa.gates = xa.exec_gates;
-        fa.hq = c->hq_set(c->expert_parity);
-        fa.hq_next = c->hq_set(c->expert_parity ^ 1);
-        c->expert_parity ^= 1;
-        fa.out = xa.out;
-        fa.k = k; fa.H = H; fa.I = I; fa.bf16 = xa.bf16;
-        fa.spin_limit = c->spin_limit;
-        fa.status = c->wait_status_dev;
-        le = launch_expert_b1_fused(fa, cfg.dtype, c->compute);
       }
       else if (which == 4) { xm.pool = xa.pool; le = launch_gateup_mfma(xm, act_m, c->at<uint16_t>(c->lay.s_q), c->at<uint16_t>(c->lay.h), c->compute); }
       else if (which == 5) { xm.pool = xa.pool; le = launch_down_mfma(xm, act_m, c->at<uint16_t>(c->lay.h), c->compute); }
@@ -1376,13 +1365,22 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   if (le == hipSuccess && e == hipSuccess) e = hipEventElapsedTime(&ms, t0, t1);
   (void)hipEventDestroy(t0);
   (void)hipEventDestroy(t1);
+#ifdef MOE_SPEC_STAGE_CLOCK
+  if (which == 7 && le == hipSuccess) {
+    unsigned long long t[12];
+    if (hipMemcpy(t, c->arena + c->lay.y, sizeof t, hipMemcpyDeviceToHost) == hipSuccess) {
+      std::fprintf(stderr, "[stage clock, last launch, 10 ns ticks since kernel start]");
+      for (int i = 1; i < 12; ++i) std::fprintf(stderr, " %llu", t[i] - t[0]);
+      std::fprintf(stderr, "\n");
+    }
+  }
+#endif
   if (le != hipSuccess) return c->hip_fail(le, "kernel launch");
   if (e != hipSuccess) return c->hip_fail(e, "timing");
   *ms_per_launch = double(ms) / reps;
   *bytes_per_launch = which == 0 || which == 3 ? int64_t(k) * 2 * I * H * wbytes
                     : which == 1 || which == 9 ? int64_t(k) * I * H * wbytes
-                    : which == 7 ? 2 * int64_t(E) * H * wbytes + int64_t(k) * H * wbytes
-                    : which == 8 ? int64_t(k) * 3 * I * H * wbytes
+                    : which == 7 ? 2 * int64_t(E) * H * wbytes + int64_t(Bm) * k * H * wbytes
                     : which == 4 ? int64_t(n_act) * 2 * I * H * wbytes
                     : which == 5 ? int64_t(n_act) * I * H * wbytes
                                  : int64_t(E) * H * wbytes;

@@ -231,8 +231,8 @@ def test_time_kernel_modes_and_their_byte_counts():
     want = {0: wl.top_k * 2 * wl.inter * wl.hidden * w, 1: wl.top_k * wl.inter * wl.hidden * w,
             2: wl.n_experts * wl.hidden * w, 3: wl.top_k * 2 * wl.inter * wl.hidden * w,
             4: 5 * 2 * wl.inter * wl.hidden * w, 5: 5 * wl.inter * wl.hidden * w,     # 5 = min(S, E, B*k) slots
-            6: wl.n_experts * wl.hidden * w, 7: (2 * wl.n_experts + wl.top_k) * wl.hidden * w,
-            8: wl.top_k * 3 * wl.inter * wl.hidden * w, 9: wl.top_k * wl.inter * wl.hidden * w}
+            6: wl.n_experts * wl.hidden * w, 7: (2 * wl.n_experts + wl.batch * wl.top_k) * wl.hidden * w,
+            9: wl.top_k * wl.inter * wl.hidden * w}
     for which, nbytes in want.items():
         ms, got = eng.time_kernel(which, 6)
         assert ms > 0 and got == nbytes, (which, ms, got, nbytes)
