@@ -1255,7 +1255,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   if (!c) return MOE_SPEC_EINVAL;
   if (which < 0 || which > 9 || which == 8 || reps < 1 || !ms_per_launch || !bytes_per_launch)
     return c->fail(MOE_SPEC_EINVAL, "bad arguments to time_kernel");
-  if (which >= 4 && c->cfg.dtype != MOE_SPEC_BF16) return c->fail(MOE_SPEC_ESTATE, "the matrix-core kernels need bf16 weights");
+  if ((which == 4 || which == 5) && c->cfg.dtype != MOE_SPEC_BF16) return c->fail(MOE_SPEC_ESTATE, "the matrix-core kernels need bf16 weights");
   if (c->token_open) return c->fail(MOE_SPEC_ESTATE, "time_kernel inside a decode step");
   const moe_spec_config &cfg = c->cfg;
   const int L = cfg.n_layers, E = cfg.n_experts, k = cfg.top_k, H = cfg.hidden, I = cfg.inter;
@@ -1298,12 +1298,14 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   const int n_act = std::min({cfg.slots_per_layer, E, Bm * k});
   ActiveList act_m{};
   ExpertArgs xm = xa;
-  if (which >= 4) {
-    std::vector<int32_t> tab(size_t(Bm) * k);
+  std::vector<int32_t> tab;                                        // outlives the launches that read its device copy
+  if (which == 4 || which == 5) {
+    tab.resize(size_t(Bm) * k);
     for (size_t f = 0; f < tab.size(); ++f) tab[f] = int32_t(f % n_act);
     act_m.n = n_act;
     for (int j = 0; j < n_act; ++j) { act_m.expert[j] = int16_t(j); act_m.slot[j] = int16_t(j); }
-    if ((e = hipMemcpy(c->arena + c->lay.pend_ids[0], tab.data(), tab.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) {
+    // on the compute stream, like the launches that follow (the stream does not synchronise with the null stream)
+    if ((e = hipMemcpyAsync(c->arena + c->lay.pend_ids[0], tab.data(), tab.size() * 4, hipMemcpyHostToDevice, c->compute)) != hipSuccess) {
       (void)hipEventDestroy(t0); (void)hipEventDestroy(t1);
       return c->hip_fail(e, "upload ids");
     }
