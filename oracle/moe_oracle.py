@@ -274,6 +274,8 @@ class OracleStats:
     cache_hits: int = 0
     cache_misses: int = 0
     h2d_bytes: int = 0
+    predictions2: int = 0      # two-layer lookahead: predictions made two layers ahead, scored like the others
+    hits2: int = 0
 
 
 @dataclass
@@ -325,7 +327,8 @@ class MoEOracle:
 
     def __init__(self, model: OracleModel, mode: int, slots_per_layer: int,
                  q_from_normalized: bool = False, predict: bool = True, predict_signal: int = 0,
-                 estimator: Optional[Estimator] = None, estimator_layers: Optional[Sequence[int]] = None):
+                 estimator: Optional[Estimator] = None, estimator_layers: Optional[Sequence[int]] = None,
+                 lookahead: int = 1):
         if slots_per_layer < model.top_k:
             raise ValueError("need at least k slots per layer")
         self.m = model
@@ -351,6 +354,17 @@ class MoEOracle:
         self.estimator = estimator
         self.estimator_layers = set(estimator_layers or []) if estimator is not None else set()
         self.diag = [LayerDiagnostics(rank_match=[0] * model.top_k) for _ in range(model.n_layers)]
+        # Multi-layer prefetching with the expert cache (the paper's Future Work names it and gives no
+        # algorithm; this is a reading).  lookahead = 2: at layer l, besides the prediction for layer l+1,
+        # layer l+2's router is applied to the same quasi-hidden vector normalised with layer l+2's gain,
+        # q2_l = LN_{l+2}(r_l + d_l), and the predicted experts are requested into layer l+2's pool as a cache
+        # hint, one layer earlier than the regular prefetch.  Nothing else changes: layer l+2 still executes
+        # what layer l+1 predicts for it, so outputs equal those of lookahead = 1; only the cache traffic and
+        # its timing differ.  Prefetching modes only.
+        if lookahead not in (1, 2):
+            raise ValueError("lookahead must be 1 or 2")
+        self.lookahead = lookahead if mode in (MODE_SPECULATIVE, MODE_PREFETCH_HINT) else 1
+        self.pending2: Dict[int, np.ndarray] = {}      # layer -> ids predicted for it two layers earlier
 
     # -- cache bookkeeping ---------------------------------------------------------
     def _request(self, layer: int, experts: Sequence[int]):
@@ -363,6 +377,7 @@ class MoEOracle:
         """A new decode step: no prediction is carried into layer 0 (cold start)."""
         self.pending = None
         self.pending_signal = None
+        self.pending2 = {}
         self.next_layer = 0
         self.stats.tokens += 1
 
@@ -444,6 +459,13 @@ class MoEOracle:
                 dg.cos_sum += float(np.dot(sig, s[b]) / np.sqrt(np.dot(sig, sig) * np.dot(s[b], s[b])))
                 dg.cos_count += 1
 
+        # recall@k of the prediction made two layers earlier (lookahead = 2)
+        if layer in self.pending2:
+            ids2 = self.pending2.pop(layer)
+            for b in range(B):
+                self.stats.hits2 += len(set(ids2[b].tolist()) & set(t_ids[b].tolist()))
+                self.stats.predictions2 += k
+
         # which experts run, with which mixing weights (Algorithm 1, the if/else at the top)
         if self.mode == MODE_SPECULATIVE and self.pending is not None:
             x_ids, x_g = self.pending
@@ -483,6 +505,14 @@ class MoEOracle:
         if self.mode in (MODE_SPECULATIVE, MODE_PREFETCH_HINT) and n_ids is not None:
             nxt = chunks_of(sorted(set(n_ids.reshape(-1).tolist())), self.S)
             self._request(layer + 1, nxt[0])
+            if self.lookahead == 2 and layer + 2 < m.n_layers:
+                ids2 = np.zeros((B, k), dtype=np.int64)
+                for b in range(B):
+                    d = layer_default_vector(m.dvecs[layer], t_ids[b], t_g[b])
+                    q2 = quasi_hidden(r[b], s[b], d, m.rms_gain[layer + 2], m.rms_eps, self.bf16, self.q_from_normalized)
+                    ids2[b], _, _ = self.route(layer + 2, q2)
+                self.pending2[layer + 2] = ids2
+                self._request(layer + 2, chunks_of(sorted(set(ids2.reshape(-1).tolist())), self.S)[0])
 
         # experts and the gate-weighted combine
         out = np.zeros((B, H))

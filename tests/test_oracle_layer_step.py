@@ -324,3 +324,65 @@ def test_prefill_is_the_standard_block_on_every_token_and_loads_every_expert():
     assert pre.stats.cache_misses == wl.n_experts and pre.stats.h2d_bytes == wl.n_experts * wl.expert_bytes
     assert pre.stats.predictions == 0
     assert pre.pools[0].slot_expert == [-1] * wl.slots          # nothing is kept for the decode cache
+
+
+def test_two_layer_lookahead_changes_traffic_and_nothing_else():
+    # lookahead = 2 adds one cache request per layer (the experts predicted for layer l+2) and a second recall
+    # counter; ids, gates and outputs are those of lookahead = 1 bit for bit, in both prefetching modes
+    wl = small_workload(n_layers=5, dtype="bf16", batch=2, tokens=4, slots=4)
+    res, ex, model = build(wl, gains="random")
+    x0, eps = W.make_inputs(wl)
+    adv = make_advance(wl, eps)
+    for mode in (O.MODE_SPECULATIVE, O.MODE_PREFETCH_HINT):
+        one = O.MoEOracle(model, mode, wl.slots)
+        two = O.MoEOracle(model, mode, wl.slots, lookahead=2)
+        tr1, tr2 = O.run_tokens(one, x0, adv), O.run_tokens(two, x0, adv)
+        for t in range(wl.tokens):
+            for l in range(wl.n_layers):
+                a, b = tr1[t][l][1], tr2[t][l][1]
+                np.testing.assert_array_equal(a.exec_ids, b.exec_ids)
+                np.testing.assert_array_equal(a.out, b.out)
+                np.testing.assert_array_equal(a.exec_gates, b.exec_gates)
+        assert (two.stats.hits, two.stats.predictions) == (one.stats.hits, one.stats.predictions)
+        assert two.stats.predictions2 == wl.top_k * wl.batch * (wl.n_layers - 2) * wl.tokens
+        assert 0 <= two.stats.hits2 <= two.stats.predictions2 and one.stats.predictions2 == 0
+        # every expert is requested at least as often; whatever the hint loaded that was not needed is extra traffic
+        assert two.stats.cache_hits + two.stats.cache_misses > one.stats.cache_hits + one.stats.cache_misses
+        assert two.stats.h2d_bytes == two.stats.cache_misses * model.expert_bytes
+    # on-demand loading has nothing to look ahead with
+    ond = O.MoEOracle(model, O.MODE_ON_DEMAND, wl.slots, lookahead=2)
+    O.run_tokens(ond, x0, adv)
+    assert ond.stats.predictions2 == 0
+
+
+def test_two_layer_lookahead_is_exact_when_the_residual_stands_still():
+    # d = 0, no residual noise and W_down = 0: r_{l+2} = r_{l+1} = r_l, so LN_{l+2}(r_l + d_l) IS s_{l+2} and the
+    # two-layer prediction must hit every time, with per-layer gains that differ (the gain of the wrong layer
+    # would miss).  With a pool as large as the expert set the hint then loads exactly what layer l+2 needs:
+    # no more transfers than without it.
+    wl = small_workload(n_layers=5, n_experts=8, top_k=2, slots=8, dtype="f32", tokens=3, res_a=1.0, res_b=0.0)
+    res, ex, model = build(wl, gains="random")
+    model.dvecs = np.zeros_like(model.dvecs)
+    H, I = wl.hidden, wl.inter
+    ex = ex.copy()
+    ex[:, :, 2 * I * H:] = 0            # W_down of every expert
+    model.experts = ex
+    x0, _ = W.make_inputs(wl)
+    adv = lambda t, l, r, out: r + out
+    two = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots, lookahead=2)
+    one = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots)
+    O.run_tokens(two, x0, adv)
+    O.run_tokens(one, x0, adv)
+    assert two.stats.hits2 == two.stats.predictions2 == wl.top_k * (wl.n_layers - 2) * wl.tokens
+    assert two.stats.cache_misses == one.stats.cache_misses
+    # the same with the gain of layer l+1 in place of layer l+2's: no longer exact
+    wrong = O.MoEOracle(model, O.MODE_SPECULATIVE, wl.slots, lookahead=2)
+    good_q = O.quasi_hidden
+    gains = model.rms_gain
+    try:
+        O.quasi_hidden = lambda r_, s_, d_, g_, eps, bf, fn=False: good_q(
+            r_, s_, d_, gains[max(0, [np.array_equal(g_, gains[i]) for i in range(len(gains))].index(True) - 1)], eps, bf, fn)
+        O.run_tokens(wrong, x0, adv)
+    finally:
+        O.quasi_hidden = good_q
+    assert wrong.stats.hits2 < wrong.stats.predictions2
