@@ -56,6 +56,9 @@ def parse():
                                                            "one more token is timed on a single thread")
     p.add_argument("--with-hint", action="store_true",
                    help="also time the prefetch-as-hint policy (prefetch the prediction, execute the true experts, re-fetch misses)")
+    p.add_argument("--with-lookahead", action="store_true",
+                   help="also time speculative mode with the two-layer lookahead (lookahead = 2: experts predicted for layer "
+                        "l+2 are requested as a cache hint one layer before the regular prefetch), on every workload of the run")
     p.add_argument("--diagnostics", action="store_true",
                    help="also collect per-layer recall@k, rank agreement and cosine similarity for the quasi-hidden "
                         "state and for the baseline signal s_l (the statistics of the paper's per-layer figures)")
@@ -107,7 +110,7 @@ class Bench:
         self.trace = load_json(TRACE_FILE) or {}
         self.codes = {"kernel": M.COPY_KERNEL, "dma": M.COPY_DMA, "dma2": M.COPY_DMA2}
         self.mode_codes = {"speculative": M.MODE_SPECULATIVE, "on_demand": M.MODE_ON_DEMAND,
-                           "prefetch_hint": M.MODE_PREFETCH_HINT}
+                           "prefetch_hint": M.MODE_PREFETCH_HINT, "speculative_lookahead2": M.MODE_SPECULATIVE}
 
     def leg(self, name, counts=None, uncounted=()):
         """counts: launches of each kernel (by a substring of its name) in this leg; uncounted: kernels the leg
@@ -141,10 +144,13 @@ class Bench:
         if headline and args.with_hint:
             engine_names["prefetch_hint"] = "kernel" if args.copy_engine == "auto" else args.copy_engine
             modes.append("prefetch_hint")
+        if args.with_lookahead:
+            engine_names["speculative_lookahead2"] = engine_names["speculative"]
+            modes.append("speculative_lookahead2")
 
         def make(mode, profile, predict=0):
             return engine_for(wl, self.mode_codes[mode], res, pool, predict_in_on_demand=predict, profile=profile,
-                              copy_engine=self.codes[engine_names[mode]])
+                              copy_engine=self.codes[engine_names[mode]], lookahead=2 if mode.endswith("lookahead2") else 0)
 
         def run_tokens(eng, t_first, n):
             out = torch.empty((B, H), dtype=torch.float32, device=dev)
@@ -199,7 +205,8 @@ class Bench:
         def summary(mode):
             tp = np.array([dt / K * 1e3 for dt, _ in results[mode]])
             dt, d = results[mode][-1]
-            return {"tpot_ms": float(tp.mean()), "tpot_ms_std": float(tp.std()), "tokens_per_s": float(B / (tp.mean() / 1e3)),
+            return {"recall_at_k_two_layers_ahead": d["hits2"] / d["predictions2"] if d["predictions2"] else None,
+                    "tpot_ms": float(tp.mean()), "tpot_ms_std": float(tp.std()), "tokens_per_s": float(B / (tp.mean() / 1e3)),
                     "h2d_gb_per_token": d["h2d_bytes"] / K / 1e9, "h2d_gbs_wall": d["h2d_bytes"] / dt / 1e9,
                     "link_frac_wall_nominal": d["h2d_bytes"] / dt / 1e9 / LINK_PEAK_GBS,
                     "expert_transfers_per_token": d["cache_misses"] / K,
@@ -213,6 +220,7 @@ class Bench:
                           "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9, "dtype": wl.dtype},
                "speculative": spec, "on_demand": ond,
                "prefetch_hint": summary("prefetch_hint") if "prefetch_hint" in modes else None,
+               "speculative_lookahead2": summary("speculative_lookahead2") if "speculative_lookahead2" in modes else None,
                "tpot_reduction_vs_on_demand": 1.0 - spec["tpot_ms"] / ond["tpot_ms"]}
 
         # ---- instrumented legs (separate contexts with timing events): compute / copy / stall breakdown, hit

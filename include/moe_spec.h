@@ -89,6 +89,12 @@ typedef struct {
   int32_t wait_spin_limit;          /* kernels that wait for another workgroup's result poll at most this
                                        often before they give up and the call after reports MOE_SPEC_EHIP;
                                        0: the default (about two seconds).  Tests force tiny values */
+  int32_t lookahead;                /* prefetching modes: 0 or 1: experts are prefetched one layer ahead (the method);
+                                       2: layer l also applies layer l+2's router to LN_{l+2}(r_l + d_l) and requests
+                                       the experts it selects into layer l+2's pool as a cache hint, one layer before
+                                       the regular prefetch (a reading of the multi-layer prefetching the paper leaves
+                                       to future work).  Executed experts and outputs do not change.  Needs the
+                                       router-based prediction (no estimator, predict_signal = 0, diagnostics = 0) */
   int32_t est_latent, est_ffn;      /* sizes of the neural estimator (Appendix A): latent size H/m and
                                        feed-forward size n*H/m, multiples of 8; 0, 0: no estimator */
   void   *device_arena;             /* dev, 256-byte aligned, >= moe_spec_arena_bytes(cfg) */
@@ -113,6 +119,7 @@ typedef struct {
                                        compute stream */
   int64_t expert_launches;          /* number of such brackets */
   int64_t prefill_tokens;           /* prompt tokens through moe_spec_prefill_layer_step, summed over layers */
+  int64_t predictions2, hits2;      /* lookahead = 2: recall@k of the predictions made two layers ahead */
 } moe_spec_stats_t;
 
 /* Optional per-step outputs, each dev [B, k] or NULL.  ids are by descending logit. */

@@ -348,11 +348,13 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
   if (wg == reporter) {
     if (tid < k) {
       const int id = sh.sel.top_i[tid];
-      const float g = static_cast<float>(sh.sel.top_e[tid] / denom);
+      const double g64 = sh.sel.top_e[tid] / denom;
+      const float g = static_cast<float>(g64);
       const size_t o = size_t(b) * k + tid;
       if (a.mb_true) a.mb_true->ids[o] = id;     // the host waits for every word it armed
       a.true_ids[o] = id;
       a.true_gates[o] = g;
+      if (a.true_gates64) a.true_gates64[o] = g64;
       if (a.user_true_ids) a.user_true_ids[o] = id;
       if (a.user_true_gates) a.user_true_gates[o] = g;
       if (a.cmp_ids) {                           // recall@k of the prediction made one layer earlier (Sec. 3.3)

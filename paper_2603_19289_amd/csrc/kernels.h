@@ -80,6 +80,7 @@ struct RoutePairArgs {
   float *s_out;                           // [B,H] s_l for the expert kernels
   uint16_t *s_out_q;                      // [B,H] the same as bf16 bit patterns, or null
   int32_t *true_ids;  float *true_gates;  // [B,k]
+  double *true_gates64;                   // [B,k] the same gates unrounded, or null
   int32_t *next_ids;  float *next_gates;  // [B,k] the prediction carried to layer l+1
   const int32_t *cmp_ids;                 // [B,k] prediction to score against this routing, or null
   LayerDiag *diag;

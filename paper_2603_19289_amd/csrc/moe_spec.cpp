@@ -73,7 +73,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, zslots, fstate, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
+      diag, zslots, fstate, la_ids, la_gates, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -97,6 +97,9 @@ const char *validate(const moe_spec_config *c) {
   if (c->est_latent % 8 || c->est_ffn % 8) return "estimator sizes must be multiples of 8";
   if (c->max_prefill_tokens < 0 || c->max_prefill_tokens > 32768) return "max_prefill_tokens out of range";
   if (c->wait_spin_limit < 0) return "wait_spin_limit must be >= 0";
+  if (c->lookahead < 0 || c->lookahead > 2) return "lookahead must be 0, 1 or 2";
+  if (c->lookahead == 2 && (c->diagnostics || c->predict_signal != 0))
+    return "lookahead = 2 needs the router-based prediction (predict_signal = 0, diagnostics = 0)";
   if (c->est_latent > MOE_SPEC_MAX_HIDDEN || c->est_ffn > 8 * MOE_SPEC_MAX_HIDDEN) return "estimator sizes too large";
   return nullptr;
 }
@@ -131,6 +134,8 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.true_ids = take(B * k * 4);
   a.true_gates = take(B * k * 4);
   a.true_gates64 = take(B * k * 8);
+  a.la_ids = take(B * k * 4);
+  a.la_gates = take(B * k * 4);
   a.h = take(B * k * I * 4);
   a.y = take(B * k * H * 4);
   a.s_q = take(B * H * 2);
@@ -174,8 +179,8 @@ struct moe_spec_ctx {
   std::vector<Pool> pools;
   std::vector<hipEvent_t> ready, done;
   std::vector<char> done_recorded, ready_recorded;
-  Mailbox *mb_true = nullptr, *mb_next = nullptr;       // pinned host
-  Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr;
+  Mailbox *mb_true = nullptr, *mb_next = nullptr, *mb_look = nullptr;       // pinned host
+  Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr, *mb_look_dev = nullptr;
   volatile unsigned int *wait_status = nullptr;         // pinned host word after the mailboxes: a kernel's bounded wait ran out
   unsigned int *wait_status_dev = nullptr;
   unsigned int spin_limit = 1u << 21;
@@ -189,6 +194,7 @@ struct moe_spec_ctx {
   std::vector<int> pending_union;               // sorted union of predicted ids (host copy)
   std::vector<int> pending_ids;                 // the predicted ids [B,k] in position order (host copy)
   ActiveList pending_wave0{};                   // slots of its first wave (already requested)
+  std::vector<int> look_ids[3];                 // lookahead = 2: ids predicted for layer l two layers earlier, at [l % 3]
 
   // statistics
   moe_spec_stats_t st{};
@@ -538,17 +544,19 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   }
   void *mb = nullptr;
   // fine-grained (coherent) pinned memory: device stores become visible to the spinning host
-  if ((e = hipHostMalloc(&mb, 2 * sizeof(Mailbox) + 64, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
+  if ((e = hipHostMalloc(&mb, 3 * sizeof(Mailbox) + 64, hipHostMallocMapped | hipHostMallocCoherent)) != hipSuccess)
     return bail(e, "pinned mailbox");
-  std::memset(mb, 0, 2 * sizeof(Mailbox) + 64);
+  std::memset(mb, 0, 3 * sizeof(Mailbox) + 64);
   c->mb_true = static_cast<Mailbox *>(mb);
   c->mb_next = c->mb_true + 1;
   void *mb_dev = nullptr;
   if ((e = hipHostGetDevicePointer(&mb_dev, mb, 0)) != hipSuccess) return bail(e, "mailbox device pointer");
   c->mb_true_dev = static_cast<Mailbox *>(mb_dev);
   c->mb_next_dev = c->mb_true_dev + 1;
-  c->wait_status = reinterpret_cast<volatile unsigned int *>(c->mb_true + 2);
-  c->wait_status_dev = reinterpret_cast<unsigned int *>(c->mb_true_dev + 2);
+  c->mb_look = c->mb_true + 2;
+  c->mb_look_dev = c->mb_true_dev + 2;
+  c->wait_status = reinterpret_cast<volatile unsigned int *>(c->mb_true + 3);
+  c->wait_status_dev = reinterpret_cast<unsigned int *>(c->mb_true_dev + 3);
   if (cfg->wait_spin_limit > 0) c->spin_limit = unsigned(cfg->wait_spin_limit);
   if ((e = c->arm_handover_slots()) != hipSuccess) return bail(e, "arm hand-over slots");
   // counters start at zero
@@ -662,6 +670,7 @@ int moe_spec_begin_token(moe_spec_ctx *c) {
   c->batch = 0;
   c->have_pending = false;
   c->pending_union.clear();
+  for (auto &v : c->look_ids) v.clear();
   c->st.tokens += 1;
   return MOE_SPEC_OK;
 }
@@ -700,8 +709,15 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   // one-kernel-per-routing path below).
   const bool fused_route = !cfg.diagnostics && route_pair_supported(H, cfg.dtype) &&
                            !(do_pred && (use_est || cfg.predict_signal == 1));
-  uint32_t ticket_next = 0;
+  uint32_t ticket_next = 0, ticket_look = 0;
   const uint32_t ticket_true = ++c->seq;
+  // lookahead = 2: a second prediction, for layer l+2, from the same quasi-hidden vector
+  const bool look2 = cfg.lookahead == 2 && prefetching && do_pred && layer + 2 < L;
+  if (cfg.lookahead == 2 && prefetching && !fused_route)
+    return c->fail(MOE_SPEC_ESTATE, "lookahead = 2 needs the router-based prediction at every layer (no estimator layers)");
+  if (look2 && !c->router_w[layer + 2]) return c->fail(MOE_SPEC_ESTATE, "resident tables of layer %d were never set", layer + 2);
+  const bool score_look = cfg.lookahead == 2 && !c->look_ids[layer % 3].empty();
+  const bool true_ids_to_host = !exec_pred || score_look;
   if (fused_route) {
     RoutePairArgs pa{};
     pa.r = static_cast<const float *>(r_dev);
@@ -722,6 +738,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     pa.s_out_q = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch ? c->at<uint16_t>(c->lay.s_q) : nullptr;
     pa.true_ids = c->at<int32_t>(c->lay.true_ids);
     pa.true_gates = c->at<float>(c->lay.true_gates);
+    pa.true_gates64 = look2 ? c->at<double>(c->lay.true_gates64) : nullptr;
     pa.next_ids = c->at<int32_t>(c->lay.pend_ids[(layer + 1) & 1]);
     pa.next_gates = c->at<float>(c->lay.pend_gates[(layer + 1) & 1]);
     pa.cmp_ids = c->have_pending ? c->at<int32_t>(c->lay.pend_ids[layer & 1]) : nullptr;
@@ -731,7 +748,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       pa.user_next_ids = outs->next_ids; pa.user_next_gates = outs->next_gates;
     }
     // the host arms the id words it will wait for; the kernel's workgroups overwrite them
-    if (!exec_pred) { pa.mb_true = c->mb_true_dev; std::memset(c->mb_true->ids, 0xff, size_t(batch) * k * 4); }
+    if (true_ids_to_host) { pa.mb_true = c->mb_true_dev; std::memset(c->mb_true->ids, 0xff, size_t(batch) * k * 4); }
     if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; std::memset(c->mb_next->ids, 0xff, size_t(batch) * k * 4); }
     __atomic_thread_fence(__ATOMIC_RELEASE);
     pa.status = c->wait_status_dev;
@@ -743,6 +760,32 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     if ((e = launch_route_pair(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
     c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
     if (do_pred) c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+    if (look2) {
+      // the same quasi-hidden vector under layer l+2's norm and router: one more launch of the one-routing kernel
+      RouteArgs la{};
+      la.r = static_cast<const float *>(r_dev);
+      la.s_in = c->at<float>(c->lay.s_buf);
+      la.w = c->router_w[layer + 2];
+      la.gain = static_cast<const float *>(c->gain[layer + 2]);
+      la.dvec = c->dvecs[layer];
+      la.d_ids = c->at<int32_t>(c->lay.true_ids);
+      la.d_gates = c->at<double>(c->lay.true_gates64);
+      la.z = c->at<double>(c->lay.z);
+      la.counter = c->at<unsigned int>(c->lay.counter);
+      la.ids_out = c->at<int32_t>(c->lay.la_ids);
+      la.gates_out = c->at<float>(c->lay.la_gates);
+      la.diag = c->at<LayerDiag>(c->lay.diag) + layer;
+      la.mailbox = c->mb_look_dev;
+      ticket_look = ++c->seq;
+      la.seq = ticket_look;
+      la.B = batch; la.H = H; la.E = E; la.k = k;
+      la.eps = cfg.rms_eps;
+      la.bf16 = cfg.dtype == MOE_SPEC_BF16;
+      la.spec = 1;
+      la.from_normalized = cfg.q_from_normalized;
+      if ((e = launch_route(la, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "lookahead routing kernel");
+      c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
+    }
   } else {
   // --- true routing of layer l (and scoring of the prediction made at l-1)
   RouteArgs ra{};
@@ -956,6 +999,32 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       if ((e = hipEventRecord(c->ready[layer + 1], c->copy)) != hipSuccess) return c->hip_fail(e, "record ready event");
       c->ready_recorded[layer + 1] = 1;
     }
+  }
+  if (score_look) {
+    // recall@k of what layer l-2 predicted for this layer; the true ids were posted before the predicted ones
+    if (exec_pred) {
+      int rc = c->wait_ids(c->mb_true, batch * k);
+      if (rc) return rc;
+      if ((rc = c->check_ids(c->mb_true->ids, batch * k))) return rc;
+    }
+    const std::vector<int> &look = c->look_ids[layer % 3];
+    for (int b = 0; b < batch; ++b)
+      for (int j = 0; j < k; ++j)
+        for (int q = 0; q < k; ++q) c->st.hits2 += look[size_t(b) * k + j] == c->mb_true->ids[size_t(b) * k + q];
+    c->st.predictions2 += int64_t(batch) * k;
+    c->look_ids[layer % 3].clear();
+  }
+  if (look2) {
+    int rc = c->wait_mailbox(c->mb_look, ticket_look);
+    if (rc) return rc;
+    if ((rc = c->check_ids(c->mb_look->ids, batch * k))) return rc;
+    std::vector<int> &look = c->look_ids[(layer + 2) % 3];
+    look.assign(c->mb_look->ids, c->mb_look->ids + batch * k);
+    std::vector<int> uni = moe_spec_ctx::sorted_union(c->mb_look->ids, batch * k);
+    uni.resize(std::min<size_t>(uni.size(), S));
+    ActiveList hinted_slots{};
+    int copies = 0;
+    if ((rc = c->request(layer + 2, uni, &hinted_slots, &copies))) return rc;
   }
 
   c->batch = batch;

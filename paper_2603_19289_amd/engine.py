@@ -23,7 +23,7 @@ class Engine:
     def __init__(self, *, n_layers, hidden, n_experts, top_k, inter, dtype, max_batch, slots, mode,
                  resident: Dict[str, np.ndarray], experts, rms_eps=1e-6, q_from_normalized=0,
                  predict_in_on_demand=1, profile=0, copy_engine=M.COPY_KERNEL, predict_signal=0, diagnostics=0, accumulate_defaults=0, estimator=None,
-                 estimator_layers=None, max_prefill_tokens=0, wait_spin_limit=0, device="cuda:0"):
+                 estimator_layers=None, max_prefill_tokens=0, wait_spin_limit=0, lookahead=0, device="cuda:0"):
         self.dev = torch.device(device)
         self.L, self.H, self.E, self.k, self.I = n_layers, hidden, n_experts, top_k, inter
         self.max_batch = max_batch
@@ -35,7 +35,7 @@ class Engine:
                        q_from_normalized=q_from_normalized, predict_in_on_demand=predict_in_on_demand,
                        profile=profile, copy_engine=copy_engine, predict_signal=predict_signal,
                        diagnostics=diagnostics, accumulate_defaults=accumulate_defaults,
-                       max_prefill_tokens=max_prefill_tokens, wait_spin_limit=wait_spin_limit,
+                       max_prefill_tokens=max_prefill_tokens, wait_spin_limit=wait_spin_limit, lookahead=lookahead,
                        est_latent=0 if estimator is None else estimator["proj"].shape[0],
                        est_ffn=0 if estimator is None else estimator["ffn_in"].shape[0])
         need = M.moe_spec_arena_bytes(cfg)

@@ -25,7 +25,7 @@ class Config(C.Structure):
                 ("predict_in_on_demand", C.c_int32), ("profile", C.c_int32), ("copy_engine", C.c_int32),
                 ("predict_signal", C.c_int32), ("diagnostics", C.c_int32),
                 ("accumulate_defaults", C.c_int32), ("max_prefill_tokens", C.c_int32),
-                ("wait_spin_limit", C.c_int32), ("est_latent", C.c_int32), ("est_ffn", C.c_int32),
+                ("wait_spin_limit", C.c_int32), ("lookahead", C.c_int32), ("est_latent", C.c_int32), ("est_ffn", C.c_int32),
                 ("device_arena", C.c_void_p), ("device_arena_bytes", C.c_size_t),
                 ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
 
@@ -36,7 +36,7 @@ class Stats(C.Structure):
                 ("h2d_bytes", C.c_int64), ("hbm_bytes_algorithmic", C.c_int64),
                 ("copy_ms", C.c_double), ("compute_ms", C.c_double), ("stall_ms", C.c_double),
                 ("wall_ms", C.c_double), ("expert_ms", C.c_double), ("expert_launches", C.c_int64),
-                ("prefill_tokens", C.c_int64)]
+                ("prefill_tokens", C.c_int64), ("predictions2", C.c_int64), ("hits2", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

@@ -51,7 +51,8 @@ def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", 
                 l2, elem = check_output(out.cpu().numpy(), want.out, wl.dtype, where)
                 worst, worst_elem = max(worst, l2), max(worst_elem, elem)
         st = eng.stats()
-        for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes"):
+        for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes",
+                     "predictions2", "hits2"):
             assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
     finally:
         eng.close()
@@ -166,6 +167,19 @@ def test_estimator_predictions(layers, dtype, B):
     use = list(range(wl.n_layers)) if layers is None else layers
     run_teacher_forced(wl, O.MODE_SPECULATIVE, oracle_kw=dict(estimator=O.Estimator(**est), estimator_layers=use),
                        estimator=est, estimator_layers=use)
+
+
+@pytest.mark.parametrize("mode", ["speculative", "prefetch_hint"])
+@pytest.mark.parametrize("dtype,B,S,engine", [("bf16", 1, 4, "COPY_DMA2"), ("f32", 3, 5, "COPY_KERNEL"), ("bf16", 20, 6, "COPY_DMA"),
+                                             ("bf16", 1, 3, "COPY_DMA2")])
+def test_two_layer_lookahead(mode, dtype, B, S, engine):
+    # layer l also requests what layer l+2's router selects on LN_{l+2}(r_l + d_l) into pool l+2 (a cache hint one
+    # layer before the regular prefetch): executed ids and outputs as without it, cache traffic and the second
+    # recall counter equal to the checker's; S = k makes the regular prefetch overwrite slots the hint just filled
+    from paper_2603_19289_amd import moe_spec as M
+    wl = small_workload(name="lookahead", n_layers=6, hidden=264, n_experts=12, top_k=3, inter=200, dtype=dtype,
+                        batch=B, tokens=5, slots=S, seed=19)
+    run_teacher_forced(wl, MODES[mode], oracle_kw=dict(lookahead=2), lookahead=2, copy_engine=getattr(M, engine))
 
 
 def test_crafted_ties_pick_the_lower_index():
