@@ -137,7 +137,9 @@ size_t moe_spec_arena_bytes(const moe_spec_config *cfg);
  * W_gate [I,H] | W_up [I,H] | W_down [H,I], row-major, in the configured dtype. */
 size_t moe_spec_expert_bytes(const moe_spec_config *cfg);
 
-/* Validates cfg (MOE_SPEC_EINVAL), then sets up events and the pinned mailbox on the current
+/* The set-up that Algorithm 1 takes as given ("Require": the model's shape, a GPU expert cache C_l per
+ * layer, experts resident on the CPU; Sec. 5.1 "Implementation Details" for the streams): validates cfg
+ * (MOE_SPEC_EINVAL), then sets up events, the pinned mailbox and the hand-over slots on the current
  * device (MOE_SPEC_EHIP if no usable GPU).  *out is written only on success. */
 int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out);
 
@@ -162,7 +164,9 @@ int moe_spec_set_estimator(moe_spec_ctx *ctx, const void *proj, const void *laye
  * low router hit rates only: Hybrid-PF).  Needs moe_spec_set_estimator first. */
 int moe_spec_set_estimator_layers(moe_spec_ctx *ctx, const uint8_t *use, int n_layers);
 
-/* Registers n_experts consecutive expert blocks of `layer`, starting at first_expert, that live at
+/* The CPU-resident expert weights {W_{l,e}} of Algorithm 1, kept in pinned host memory so that copies to
+ * the GPU can run asynchronously (Sec. 5.1 "Implementation Details"; only experts are offloaded).
+ * Registers n_experts consecutive expert blocks of `layer`, starting at first_expert, that live at
  * pinned_host (host, page-locked: MOE_SPEC_EINVAL otherwise).  bytes must equal
  * n_experts * moe_spec_expert_bytes.  Nothing is copied: the pool is read at prefetch time. */
 int moe_spec_load_host_experts(moe_spec_ctx *ctx, int layer, int first_expert, int n_experts,
@@ -171,7 +175,9 @@ int moe_spec_load_host_experts(moe_spec_ctx *ctx, int layer, int first_expert, i
 /* Starts a decode step: drops the carried prediction, so layer 0 is a cold start (Algorithm 1). */
 int moe_spec_begin_token(moe_spec_ctx *ctx);
 
-/* One MoE block.  r_dev [batch,H] float (post-attention residual r_l), out_dev [batch,H] float
+/* One MoE block with expert prefetch, Algorithm 1 (decode): true routing TopK(Gate_l(X)), GetNextExperts
+ * (Sec. 3.1-3.3: d_l, q_l, layer l+1's router), WaitAndPrefetch of the predicted experts, MoE_l on the
+ * experts chosen by the mode (Sec. 4).  r_dev [batch,H] float (post-attention residual r_l), out_dev [batch,H] float
  * (O_l, valid in compute-stream order).  Layers must be stepped 0,1,...,L-1 after begin_token with
  * the same batch (MOE_SPEC_ESTATE otherwise, also when a layer's tables or experts were never
  * registered).  outs may be NULL.  Asynchronous except for the hand-over of expert ids to the host.
@@ -237,7 +243,8 @@ int moe_spec_layer_diagnostics(moe_spec_ctx *ctx, int layer, moe_spec_layer_diag
  * are the per-expert default vectors d_{l,e} of Sec. 3.1.  Synchronises the compute stream. */
 int moe_spec_read_default_vectors(moe_spec_ctx *ctx, int layer, float *mean_dev, int64_t *counts_host);
 
-/* Synchronises both streams, then copies the counters. */
+/* The figures the paper's evaluation reports (Sec. 3.3 recall@k; Sec. 5.1.2 time per output token and its
+ * compute / copy / idle parts).  Synchronises both streams, then copies the counters. */
 int moe_spec_stats(moe_spec_ctx *ctx, moe_spec_stats_t *out);
 
 /* Empties the slot cache, drops the carried prediction and zeroes the statistics. */

@@ -200,19 +200,20 @@ __device__ __forceinline__ double select_gates(int k, SelectShared &sel, int tid
 // top-k, the default-vector sum), so that nothing but the 8-byte logits crosses between workgroups.
 // Workgroup 0 of a token finishes the prediction; the last one reports the true routing, off the path
 // that the prediction waits on.
-template <typename WT, int SPLIT, int NCH>
+template <typename WT, int SPLIT, int NCH, int ROWS>
 __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs a) {
+  static_assert(ROWS == 1 || SPLIT == 1, "several rows per wavefront only with one wavefront per row");
   extern __shared__ double vec[];              // [H] the router input being built, double precision
   __shared__ RouteShared sh;
   using P = Packed<WT>;
   using Raw = typename P::Raw;
   constexpr int VN = P::N;
-  constexpr int RPW = kWaves / SPLIT;          // rows per workgroup
+  constexpr int RPW = kWaves / SPLIT * ROWS;   // rows per workgroup
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int wg = blockIdx.x, b = blockIdx.y;
   const int H = a.H, E = a.E, k = a.k;
-  const int row = wg * RPW + wave / SPLIT, part = wave % SPLIT;
+  const int row = wg * RPW + wave / SPLIT * ROWS, part = wave % SPLIT;   // this wavefront's (first) row
   const bool pred = a.w_next != nullptr;
   const WT *wt = static_cast<const WT *>(a.w_true);
   const WT *wn = static_cast<const WT *>(a.w_next);
@@ -232,8 +233,8 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
       g0[x] = g.x; g0[x + 1] = g.y; g0[x + 2] = g.z; g0[x + 3] = g.w;
     }
   }
-  Raw rt[NCH], rn[NCH];
-  if (row < E) {
+  Raw rt[NCH], rn[NCH];                        // one row per wavefront: both routers' rows travel in registers
+  if (ROWS == 1 && row < E) {
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
       const int c = ((ch * SPLIT + part) * kWave + lane) * VN;
@@ -290,27 +291,45 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     __syncthreads();
   }
   STAGE(1);
-  // ---- logits of a router; one row per SPLIT wavefronts
-  auto row_logit = [&](const Raw (&w)[NCH]) {
+  // ---- logits of a router: one row per SPLIT wavefronts from the registers loaded above, or (batches) ROWS
+  //      rows per wavefront read where they are used, the router being in L2 after the first tokens
+  auto dot_row = [&](const Raw (&w)[NCH]) {
     double acc = 0.0;
-    if (row < E) {
 #pragma unroll
-      for (int ch = 0; ch < NCH; ++ch) {
-        const int c = ((ch * SPLIT + part) * kWave + lane) * VN;
-        if (c < H) {
-          float wf[VN];
-          P::unpack(w[ch], wf);
+    for (int ch = 0; ch < NCH; ++ch) {
+      const int c = ((ch * SPLIT + part) * kWave + lane) * VN;
+      if (c < H) {
+        float wf[VN];
+        P::unpack(w[ch], wf);
 #pragma unroll
-          for (int x = 0; x < VN; ++x) acc += double(wf[x]) * vec[c + x];
-        }
+        for (int x = 0; x < VN; ++x) acc += double(wf[x]) * vec[c + x];
       }
     }
     return wave_sum(acc);
   };
-  auto publish_rows = [&](double acc, unsigned long long *slots) {
-    if (SPLIT == 1) {
+  auto publish_rows = [&](const Raw (&held)[NCH], const WT *wmat, unsigned long long *slots) {
+    if (ROWS > 1) {
+      Raw w[2][NCH];
+      auto fetch = [&](int rr, Raw (&dst)[NCH]) {
+        const int rclamped = min(row + rr, E - 1);
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+          const int c = (ch * kWave + lane) * VN;
+          dst[ch] = *reinterpret_cast<const Raw *>(wmat + size_t(rclamped) * H + (c < H ? c : 0));
+        }
+      };
+      fetch(0, w[0]);
+#pragma unroll
+      for (int rr = 0; rr < ROWS; ++rr) {
+        if (rr + 1 < ROWS) fetch(rr + 1, w[(rr + 1) & 1]);
+        const double acc = dot_row(w[rr & 1]);
+        if (lane == 0 && row + rr < E) publish64(slots + size_t(b) * E + row + rr, acc);
+      }
+    } else if (SPLIT == 1) {
+      const double acc = row < E ? dot_row(held) : 0.0;
       if (lane == 0 && row < E) publish64(slots + size_t(b) * E + row, acc);
     } else {
+      const double acc = row < E ? dot_row(held) : 0.0;
       if (lane == 0) sh.part[wave] = acc;
       __syncthreads();
       if (tid < RPW && wg * RPW + tid < E) {
@@ -321,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
       }
     }
   };
-  publish_rows(row_logit(rt), a.z_true);
+  publish_rows(rt, wt, a.z_true);
   STAGE(2);
   const int reporter = gridDim.x - 1;
   if (!pred && wg != reporter) return;
@@ -447,7 +466,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     __syncthreads();
   }
   STAGE(7);
-  publish_rows(row_logit(rn), a.z_pred);
+  publish_rows(rn, wn, a.z_pred);
   STAGE(8);
   if (wg != 0) return;
 
@@ -486,32 +505,32 @@ hipError_t prepare_kernel(K kernel, size_t lds, int *blocks_per_cu) {
   return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, kernel, kBlock, lds);
 }
 
-template <typename WT, int SPLIT, int NCH>
+template <typename WT, int SPLIT, int NCH, int ROWS>
 hipError_t launch_route_pair_n(const RoutePairArgs &a, hipStream_t st) {
-  constexpr int RPW = kWaves / SPLIT;
+  constexpr int RPW = kWaves / SPLIT * ROWS;
   const size_t lds = size_t(a.H) * sizeof(double);
   const int n_wg = (a.E + RPW - 1) / RPW;
   static int blocks_per_cu = -1;               // per instantiation
   static size_t checked_lds = 0;
   if (blocks_per_cu < 0 || lds > checked_lds) {
     int n = 0;
-    hipError_t e = prepare_kernel(route_pair_kernel<WT, SPLIT, NCH>, lds, &n);
+    hipError_t e = prepare_kernel(route_pair_kernel<WT, SPLIT, NCH, ROWS>, lds, &n);
     if (e != hipSuccess) return e;
     blocks_per_cu = n;
     checked_lds = lds;
   }
   // the workgroups of a token wait for one another: they must fit on the device together
   if (long(n_wg) > long(blocks_per_cu) * g_compute_units) return hipErrorLaunchOutOfResources;
-  hipLaunchKernelGGL((route_pair_kernel<WT, SPLIT, NCH>), dim3(n_wg, a.B), dim3(kBlock), lds, st, a);
+  hipLaunchKernelGGL((route_pair_kernel<WT, SPLIT, NCH, ROWS>), dim3(n_wg, a.B), dim3(kBlock), lds, st, a);
   return hipGetLastError();
 }
 
-template <typename WT, int SPLIT>
+template <typename WT, int SPLIT, int ROWS>
 hipError_t launch_route_pair_s(const RoutePairArgs &a, int need, hipStream_t st) {
-  if (need <= 1) return launch_route_pair_n<WT, SPLIT, 1>(a, st);
-  if (need <= 2) return launch_route_pair_n<WT, SPLIT, 2>(a, st);
-  if (need <= 4) return launch_route_pair_n<WT, SPLIT, 4>(a, st);
-  if (need <= 8) return launch_route_pair_n<WT, SPLIT, 8>(a, st);
+  if (need <= 1) return launch_route_pair_n<WT, SPLIT, 1, ROWS>(a, st);
+  if (need <= 2) return launch_route_pair_n<WT, SPLIT, 2, ROWS>(a, st);
+  if (need <= 4) return launch_route_pair_n<WT, SPLIT, 4, ROWS>(a, st);
+  if (need <= 8) return launch_route_pair_n<WT, SPLIT, 8, ROWS>(a, st);
   return hipErrorInvalidValue;
 }
 
@@ -522,10 +541,15 @@ hipError_t launch_route_pair_t(const RoutePairArgs &a, hipStream_t st) {
   const int need4 = (chunks + 4 * kWave - 1) / (4 * kWave);    // four wavefronts per row
   // One token: a workgroup per router row, E workgroups (measured on 128 experts of 2048 columns: 15.4 us per
   // launch against 19.1 us with four rows per workgroup).  A batch: its tokens already fill the device, and
-  // every workgroup repeats the token's norm, top-k and default-vector sum, so four rows per workgroup
-  // (32 tokens: 47 us against 103 us)
-  if (a.B > 1 && need1 <= 8) return launch_route_pair_s<WT, 1>(a, need1, st);
-  return launch_route_pair_s<WT, 4>(a, need4, st);
+  // every workgroup repeats its token's norm, top-k and default-vector sum, so the more tokens, the more rows
+  // per workgroup: 4 up to about 512 workgroups per launch, 16 beyond (32 tokens x 128 experts: 29 us with 16
+  // rows per workgroup, 33 us with 8, 46 us with 4; 64 tokens: 45, 59, 89 us).
+  if (a.B > 1 && need1 <= 8) {
+    const long wgs4 = long(a.B) * ((a.E + 3) / 4);
+    if (wgs4 <= 512) return launch_route_pair_s<WT, 1, 1>(a, need1, st);
+    return launch_route_pair_s<WT, 1, 4>(a, need1, st);
+  }
+  return launch_route_pair_s<WT, 4, 1>(a, need4, st);
 }
 
 }  // namespace

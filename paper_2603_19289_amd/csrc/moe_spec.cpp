@@ -927,9 +927,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   const bool use_mfma = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch;
 
   // --- cache waves: make resident (unless prefetched), wait, run
-  TimedSpan *sp_stall = c->open_span(2, c->compute);
-  bool stall_open = sp_stall != nullptr;
-  TimedSpan *sp_exec = nullptr;
+  // profile = 1: every cache wave's wait for its copies is a stall span, its kernels a compute span
   for (size_t w0 = 0, wave = 0; w0 < exec_union.size(); w0 += S, ++wave) {
     ActiveList act{};
     int copies = 0;
@@ -943,9 +941,12 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       if (rc) return rc;
       need_wait = copies > 0 || (hinted && wave == 0);
     }
-    if (need_wait && (e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess)
-      return c->hip_fail(e, "compute stream wait");
-    if (stall_open) { c->close_span(sp_stall, c->compute); stall_open = false; sp_exec = c->open_span(0, c->compute); }
+    if (need_wait) {
+      TimedSpan *sp_stall = c->open_span(2, c->compute);
+      if ((e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
+      c->close_span(sp_stall, c->compute);
+    }
+    TimedSpan *sp_exec = c->open_span(0, c->compute);
     TimedSpan *sp_gu = c->open_span(3, c->compute);
     if (fast_b1) {
       // batch 1: the k executed experts are one wave; hand the kernels the slots in position order
@@ -977,9 +978,13 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     if ((e = hipEventRecord(c->done[layer], c->compute)) != hipSuccess) return c->hip_fail(e, "record done event");
     c->done_recorded[layer] = 1;
     c->st.hbm_bytes_algorithmic += int64_t(act.n) * int64_t(c->expert_bytes);
+    c->close_span(sp_exec, c->compute);
   }
-  if (!fast_b1 && (e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
-  c->close_span(sp_exec, c->compute);
+  if (!fast_b1) {
+    TimedSpan *sp_comb = c->open_span(0, c->compute);
+    if ((e = launch_combine(xa, c->compute)) != hipSuccess) return c->hip_fail(e, "combine kernel");
+    c->close_span(sp_comb, c->compute);
+  }
 
   // --- prefetch the first wave of the predicted experts of layer l+1
   c->have_pending = do_pred;

@@ -335,13 +335,13 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   if (a.mailbox) __threadfence_system();
   __syncthreads();
   if (tid == 0) {
-    *arrivals = 0u;
+    __hip_atomic_store(arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // the ids are complete when every group is: the last group to finish tells the host
     bool all_done = true;
     if (gridDim.y > 1) {
       __threadfence();
       all_done = atomicAdd(a.counter, 1u) == gridDim.y - 1;
-      if (all_done) { __threadfence(); *a.counter = 0u; }
+      if (all_done) { __threadfence(); __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
     }
     if (all_done && a.mailbox)
       __hip_atomic_store(&a.mailbox->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);

@@ -117,3 +117,15 @@ def test_bench_refuses_more_than_one_gpu(monkeypatch, capsys):
         bench.main()
     assert ei.value.code == 2
     assert "ONE GPU" in capsys.readouterr().err
+
+
+@pytest.mark.gpu
+def test_c_client_of_the_library_runs():
+    """csrc/abi_demo.c uses the boundary from plain C, without Python or torch: three modes, prefill, error returns,
+    counter identities, run-to-run bit equality.  It ran as its own process before this session touched the GPU
+    (tests/conftest.py); here its verdict is checked."""
+    from tests.conftest import C_CLIENT
+    if not C_CLIENT["ran"]:
+        pytest.skip("the C client did not run (not built, or GPU tests were not selected with -m gpu)")
+    assert C_CLIENT["rc"] == 0, C_CLIENT["output"]
+    assert "abi demo ok" in C_CLIENT["output"]

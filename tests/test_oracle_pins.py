@@ -186,32 +186,61 @@ def test_lru_never_evicts_a_member_of_the_request_and_fills_empty_slots_first():
     assert (h, m) == (1, 2) and 5 in p.slot_expert and set(p.slot_expert) == {5, 8, 9}
 
 
-def _reference_lru(n_slots, requests):
-    """Independent restatement with a recency-ordered list of (stamp, slot) pairs."""
-    slots = [None] * n_slots
-    stamp = [-1] * n_slots
-    log = []
-    for t, req in enumerate(requests, start=1):
+def _textbook_lru(n_slots, experts):
+    """The textbook cache for requests of ONE expert at a time (no ties to break): an ordered dictionary, a hit
+    moves the key to the fresh end, a miss on a full cache drops the key at the stale end."""
+    from collections import OrderedDict
+    cache, log = OrderedDict(), []
+    for e in experts:
+        if e in cache:
+            cache.move_to_end(e)
+            log.append((1, 0))
+        else:
+            if len(cache) == n_slots:
+                cache.popitem(last=False)
+            cache[e] = True
+            log.append((0, 1))
+    return log
+
+
+@pytest.mark.parametrize("S,E", [(2, 5), (4, 8), (16, 128)])
+def test_lru_equals_the_textbook_cache_on_single_expert_requests(S, E):
+    rng = np.random.default_rng(S + E)
+    seq = rng.integers(0, E, size=600).tolist()
+    p = O.LRUPool(S)
+    assert [p.request([e])[:2] for e in seq] == _textbook_lru(S, seq)
+
+
+def _lru_by_expert_records(n_slots, requests):
+    """The policy restated around the experts instead of the slots: a record (time of last request, slot) per
+    resident expert and a sorted list of free slots.  Whole sets are requested, so experts touched together share
+    a time; a miss takes the lowest free slot, else evicts the resident expert outside the request with the
+    oldest time (lowest slot among equally old ones)."""
+    resident, free, log = {}, list(range(n_slots)), []
+    for now, req in enumerate(requests, start=1):
         req = sorted(set(req))
-        hit = [e for e in req if e in slots]
-        for e in hit:
-            stamp[slots.index(e)] = t
-        miss = [e for e in req if e not in slots]
-        for e in miss:
-            order = sorted((stamp[i], i) for i in range(n_slots) if slots[i] not in req)
-            i = order[0][1]
-            slots[i], stamp[i] = e, t
-        log.append((len(hit), len(miss)))
+        hits = [e for e in req if e in resident]
+        for e in hits:
+            resident[e] = (now, resident[e][1])
+        misses = [e for e in req if e not in resident]
+        for e in misses:
+            if free:
+                slot = free.pop(0)
+            else:
+                victim = min((x for x in resident if x not in req), key=lambda x: resident[x])
+                slot = resident.pop(victim)[1]
+            resident[e] = (now, slot)
+        log.append((len(hits), len(misses)))
     return log
 
 
 @pytest.mark.parametrize("S,E,qmax", [(4, 8, 2), (3, 8, 3), (8, 32, 8), (16, 128, 8)])
-def test_lru_against_reference_on_random_requests(S, E, qmax):
+def test_lru_against_the_expert_record_restatement_on_random_requests(S, E, qmax):
     rng = np.random.default_rng(S * 100 + E)
     reqs = [rng.choice(E, size=rng.integers(1, qmax + 1), replace=False).tolist() for _ in range(400)]
     p = O.LRUPool(S)
     got = [p.request(r)[:2] for r in reqs]
-    assert got == _reference_lru(S, reqs)
+    assert got == _lru_by_expert_records(S, reqs)
 
 
 def test_lru_pool_as_large_as_the_expert_set_misses_each_expert_once():
