@@ -8,7 +8,9 @@ Qwen3-30B-A3B-shaped workload; on-demand loading is measured beside it on the sa
 After the headline workload two more are timed in the same run, shorter: the batch-32 workload (the
 matrix-core expert path) and the tiny float32 one.
 
-Prints one JSON line (see README for the fields).
+Prints one JSON line: metric, value (tokens/s), ms_per_step (TPOT), both modes' figures, the instrumented
+compute / copy / stall breakdown, `roofline` (dominant kernel, every hot kernel, the layer step), the paper's
+analytic model against the measurement, `cpu_baseline`, and the same for the other workloads of the run.
 """
 import argparse
 import json
@@ -443,7 +445,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "run with --gpus 1.  How the path would shard is described in DESIGN.md.", file=sys.stderr)
+              "run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     b = Bench(args)
     W = b.W

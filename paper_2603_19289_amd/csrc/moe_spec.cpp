@@ -73,7 +73,7 @@ struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 
 
 struct ArenaLayout {
   size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
-      diag, zslots, fstate, la_ids, la_gates, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
+      diag, zslots, zslots_end, la_ids, la_gates, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
 const char *validate(const moe_spec_config *c) {
@@ -120,9 +120,9 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.bench_ids = take(256);
   // hand-over slots of the fused routing kernel: two sets each of true and predicted logits [B,E], all
-  // ones when armed; then the token-group counters (zero)
+  // ones when armed
   a.zslots = take(size_t(4) * B * E * 8);
-  a.fstate = take(256);
+  a.zslots_end = off;
   a.dacc_sum = take(c->accumulate_defaults ? size_t(c->n_layers) * E * H * 8 : 0);
   a.dacc_cnt = take(c->accumulate_defaults ? size_t(c->n_layers) * E * 8 : 0);
   a.dacc_end = off;
@@ -443,8 +443,7 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
   hipError_t arm_handover_slots() {
-    hipError_t e = hipMemsetAsync(arena + lay.zslots, 0xff, lay.fstate - lay.zslots, compute);
-    if (e == hipSuccess) e = hipMemsetAsync(arena + lay.fstate, 0, 256, compute);
+    hipError_t e = hipMemsetAsync(arena + lay.zslots, 0xff, lay.zslots_end - lay.zslots, compute);
     route_parity = 0;
     if (wait_status) *wait_status = 0;
     return e;
