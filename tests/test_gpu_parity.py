@@ -111,6 +111,9 @@ def test_edge_shapes(mode):
     run_teacher_forced(small_workload(name="max_inter", n_layers=2, hidden=64, inter=32768, n_experts=2, top_k=1, slots=1,
                                       batch=2, tokens=1), MODES[mode])       # 128 KB of LDS in the down kernel
     run_teacher_forced(small_workload(name="max_batch", batch=64, n_experts=16, top_k=2, slots=8, tokens=2, dtype="f32"), MODES[mode])
+    # a batch large enough for sixteen router rows per workgroup, with a ragged last workgroup (50 = 3 * 16 + 2)
+    run_teacher_forced(small_workload(name="many_rows_per_workgroup", batch=48, n_experts=50, top_k=5, slots=50, tokens=2,
+                                      hidden=136, inter=40), MODES[mode])
 
 
 @pytest.mark.parametrize("dtype,H", [("bf16", 4608), ("f32", 4352), ("bf16", 8192), ("f32", 8192)])
