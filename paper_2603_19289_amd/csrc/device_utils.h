@@ -133,6 +133,54 @@ __device__ __forceinline__ T wave_sum(T v) {
   return (readlane(v, 0) + readlane(v, 16)) + (readlane(v, 32) + readlane(v, 48));
 }
 
+// ---- Hand-over slots: "the data is the flag".  A slot of global memory holds all ones (a NaN pattern no
+// result can have) until its producer overwrites it with one relaxed device-scope atomic store; consumers read
+// it with relaxed device-scope atomic loads until it no longer holds that pattern.  Each slot is a single
+// atomic object: nothing has to be ordered against anything else.
+constexpr unsigned long long kEmpty64 = ~0ull;
+
+__device__ __forceinline__ void raise_status(unsigned int *status) {      // a word in pinned host memory
+  __hip_atomic_store(status, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__device__ __forceinline__ void publish64(unsigned long long *slot, double v) {
+  if (!(v == v)) v = -INFINITY;                // a result that is not a number must not look like an empty slot
+  v += 0.0;                                    // -0.0 becomes +0.0: equal logits must be equal bit patterns
+  __hip_atomic_store(slot, static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
+                     __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void arm64(unsigned long long *slot) {
+  __hip_atomic_store(slot, kEmpty64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ unsigned long long peek64(const unsigned long long *slot) {
+  return __hip_atomic_load(slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Waits (boundedly) until the slot holds a value.  A look at memory takes about a microsecond to come back;
+// four looks are kept in flight a few hundred nanoseconds apart, so that a value is noticed that soon after
+// it lands instead of a whole round trip later.
+__device__ __forceinline__ unsigned long long await64(const unsigned long long *slot, unsigned int limit,
+                                                      unsigned int *status) {
+  unsigned long long v = peek64(slot);
+  for (unsigned int spins = 0; v == kEmpty64; spins += 4) {
+    if (spins >= limit) { raise_status(status); break; }
+    const unsigned long long v0 = peek64(slot);
+    __builtin_amdgcn_s_sleep(5);
+    const unsigned long long v1 = peek64(slot);
+    __builtin_amdgcn_s_sleep(5);
+    const unsigned long long v2 = peek64(slot);
+    __builtin_amdgcn_s_sleep(5);
+    const unsigned long long v3 = peek64(slot);
+    if (v0 != kEmpty64) v = v0;
+    else if (v1 != kEmpty64) v = v1;
+    else if (v2 != kEmpty64) v = v2;
+    else v = v3;
+  }
+  return v;
+}
+
 // In-register rank sort of one token's logits.  Every wavefront holds all candidates in
 // registers (element i = r*64 + lane, R per lane) and counts, for each of its candidates, how
 // many candidates broadcast from source lanes [src_begin, src_end) rank before it: larger logit

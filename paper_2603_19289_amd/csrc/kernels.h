@@ -12,11 +12,11 @@ constexpr int kRouteBlock = 256;        // threads per workgroup of the routing 
 constexpr int kRouteRowsPerBlock = 4;   // one router row per wavefront
 constexpr int kMailboxIds = kMaxBatch * kMaxTopK;
 
-// Pinned host mailbox written by the last workgroup of a routing kernel.
+// Pinned host mailbox written by the reporting workgroups of a routing kernel.  Every id word is its own flag:
+// the host sets the words it is about to wait for to -1 before the launch and spins until none is -1.
 struct Mailbox {
   int32_t ids[kMailboxIds];   // [B, k] expert ids by descending logit
-  uint32_t seq;               // written last; the host spins until it equals the step's ticket
-  uint32_t pad[15];
+  uint32_t pad[16];
 };
 
 // Per-layer statistics of the predictions made for a layer, accumulated by the routing kernel
@@ -46,8 +46,11 @@ struct RouteArgs {
   const void *dvec;           // spec: [E,H] default vectors of layer l
   const int32_t *d_ids;       // spec: [B,k] true ids of layer l
   const double *d_gates;      // spec: [B,k] true gates of layer l
-  double *z;                  // [B,E] logits scratch
-  unsigned int *counter;      // [1 + kMaxBatch] arrival counters (groups done, then one per token group), zero between launches
+  unsigned long long *slots;  // [B,E] logit hand-over slots of this launch, armed (all ones)
+  unsigned long long *arm_a, *arm_b;   // the two sets of slots the next routing launch may use, armed by this launch
+  int arm_count;              // slots per set (largest batch * E)
+  unsigned int spin_limit;    // bound of the finishing workgroup's wait for a logit
+  unsigned int *status;       // pinned host word raised when that wait runs out
   float *vec_out;             // [B,H] normalised (and rounded) vector, or null
   uint16_t *vec_out_q;        // [B,H] the same as bf16 bit patterns (bf16 mode), or null
   int32_t *ids_out;           // [B,k]
@@ -59,8 +62,7 @@ struct RouteArgs {
   int rank_stats;             // also count per-rank agreement
   int32_t *user_ids;          // optional copies for the caller
   float *user_gates;
-  Mailbox *mailbox;           // pinned host, or null
-  uint32_t seq;
+  Mailbox *mailbox;           // pinned host, or null: ids[B*k] words the host set to -1 and waits for
   int B, H, E, k;
   float eps;
   int bf16, spec, from_normalized, tok_tile;

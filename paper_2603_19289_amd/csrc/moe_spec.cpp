@@ -72,7 +72,7 @@ constexpr int kDmaQueues = 2;        // copy_engine 2: the caller's copy stream 
 struct TimedSpan { hipEvent_t a, b; int kind; };   // kind 0 compute, 1 copy, 2 stall, 3 expert FFN of one cache wave
 
 struct ArenaLayout {
-  size_t slots, s_buf, z, counter, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
+  size_t slots, s_buf, true_ids, true_gates, true_gates64, pend_ids[2], pend_gates[2],
       diag, zslots, zslots_end, la_ids, la_gates, h, y, bench_ids, s_q, sig, est_u, est_t, est_v, dacc_sum, dacc_cnt, dacc_end, tr_begin, tr_end, pf_s, pf_sq, pf_ids, pf_gates, pf_y, pf_hq, pf_pos, pf_count, total;
 };
 
@@ -115,7 +115,6 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   auto take = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
   a.slots = take(size_t(c->n_layers) * c->slots_per_layer * align_up(expert_bytes_of(c), 256));
   // state that lives from call to call
-  a.counter = take((1 + kMaxBatch) * sizeof(unsigned int));
   for (int i = 0; i < 2; ++i) { a.pend_ids[i] = take(B * k * 4); a.pend_gates[i] = take(B * k * 4); }
   a.diag = take(size_t(c->n_layers) * sizeof(LayerDiag));
   a.bench_ids = take(256);
@@ -130,7 +129,6 @@ ArenaLayout layout_of(const moe_spec_config *c) {
   // that moe_spec_layer_step_static keeps in the library's static array instead.
   a.tr_begin = off;
   a.s_buf = take(B * H * 4);
-  a.z = take(B * E * 8);
   a.true_ids = take(B * k * 4);
   a.true_gates = take(B * k * 4);
   a.true_gates64 = take(B * k * 8);
@@ -184,7 +182,6 @@ struct moe_spec_ctx {
   volatile unsigned int *wait_status = nullptr;         // pinned host word after the mailboxes: a kernel's bounded wait ran out
   unsigned int *wait_status_dev = nullptr;
   unsigned int spin_limit = 1u << 21;
-  uint32_t seq = 0;
   uint32_t route_parity = 0;                            // which set of logit slots the next fused routing launch uses
 
   // token state
@@ -265,27 +262,8 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
 
-  // Spin until the mailbox shows this ticket.  Bounded; also notices a failed stream.
-  int wait_mailbox(const Mailbox *mb, uint32_t ticket) {
-    const volatile uint32_t *flag = &mb->seq;
-    auto start = std::chrono::steady_clock::now();
-    unsigned long spins = 0;
-    while (*flag != ticket) {
-      __builtin_ia32_pause();
-      if ((++spins & 0xfffff) == 0) {
-        hipError_t q = hipStreamQuery(compute);
-        if (q != hipSuccess && q != hipErrorNotReady) return hip_fail(q, "compute stream failed while routing");
-        if (q == hipSuccess && *flag != ticket)
-          return fail(MOE_SPEC_EHIP, "routing kernel finished without posting expert ids");
-        if (std::chrono::steady_clock::now() - start > std::chrono::seconds(30))
-          return fail(MOE_SPEC_EHIP, "timed out waiting for expert ids from the routing kernel");
-      }
-    }
-    __atomic_thread_fence(__ATOMIC_ACQUIRE);
-    return MOE_SPEC_OK;
-  }
-
-  // The fused routing kernel overwrites id words that the host armed with -1: spin until all n are there.
+  // The routing kernels overwrite id words that the host armed with -1 (arm_ids): spin until all n are there.
+  // Bounded; also notices a failed stream.
   int wait_ids(const Mailbox *mb, int n) {
     const volatile int32_t *ids = mb->ids;
     auto start = std::chrono::steady_clock::now();
@@ -434,6 +412,22 @@ struct moe_spec_ctx {
     return MOE_SPEC_OK;
   }
 
+  // Hand-over slots, their bound and the status word of one launch of the one-routing kernel; the launch uses
+  // the current set of logit slots and arms both sets of the other parity, like the fused kernel.
+  void prep_route(RouteArgs &ra) {
+    ra.slots = zslot_set(0, route_parity);
+    ra.arm_a = zslot_set(0, route_parity ^ 1);
+    ra.arm_b = zslot_set(1, route_parity ^ 1);
+    ra.arm_count = cfg.max_batch * cfg.n_experts;
+    ra.spin_limit = spin_limit;
+    ra.status = wait_status_dev;
+    route_parity ^= 1;
+  }
+  static void arm_ids(Mailbox *mb, int n) {
+    std::memset(mb->ids, 0xff, size_t(n) * 4);
+    __atomic_thread_fence(__ATOMIC_RELEASE);
+  }
+
   // A waiter inside a fused kernel gave up: its results are not to be trusted, and the hand-over slots are
   // in an unknown state until moe_spec_reset re-arms them.
   int check_waits() {
@@ -559,7 +553,6 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
   if (cfg->wait_spin_limit > 0) c->spin_limit = unsigned(cfg->wait_spin_limit);
   if ((e = c->arm_handover_slots()) != hipSuccess) return bail(e, "arm hand-over slots");
   // counters start at zero
-  if ((e = hipMemsetAsync(c->arena + lay.counter, 0, (1 + kMaxBatch) * sizeof(unsigned int), c->compute)) != hipSuccess) return bail(e, "clear counter");
   if ((e = hipMemsetAsync(c->arena + lay.diag, 0, size_t(L) * sizeof(LayerDiag), c->compute)) != hipSuccess) return bail(e, "clear counters");
   if (cfg->accumulate_defaults) {
     if ((e = hipMemsetAsync(c->arena + lay.dacc_sum, 0, lay.dacc_end - lay.dacc_sum, c->compute)) != hipSuccess) return bail(e, "clear sums");
@@ -708,8 +701,6 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   // one-kernel-per-routing path below).
   const bool fused_route = !cfg.diagnostics && route_pair_supported(H, cfg.dtype) &&
                            !(do_pred && (use_est || cfg.predict_signal == 1));
-  uint32_t ticket_next = 0, ticket_look = 0;
-  const uint32_t ticket_true = ++c->seq;
   // lookahead = 2: a second prediction, for layer l+2, from the same quasi-hidden vector
   const bool look2 = cfg.lookahead == 2 && prefetching && do_pred && layer + 2 < L;
   if (cfg.lookahead == 2 && prefetching && !fused_route)
@@ -747,9 +738,8 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       pa.user_next_ids = outs->next_ids; pa.user_next_gates = outs->next_gates;
     }
     // the host arms the id words it will wait for; the kernel's workgroups overwrite them
-    if (true_ids_to_host) { pa.mb_true = c->mb_true_dev; std::memset(c->mb_true->ids, 0xff, size_t(batch) * k * 4); }
-    if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; std::memset(c->mb_next->ids, 0xff, size_t(batch) * k * 4); }
-    __atomic_thread_fence(__ATOMIC_RELEASE);
+    if (true_ids_to_host) { pa.mb_true = c->mb_true_dev; moe_spec_ctx::arm_ids(c->mb_true, batch * k); }
+    if (do_pred && prefetching) { pa.mb_next = c->mb_next_dev; moe_spec_ctx::arm_ids(c->mb_next, batch * k); }
     pa.status = c->wait_status_dev;
     pa.B = batch; pa.H = H; pa.E = E; pa.k = k;
     pa.eps = cfg.rms_eps;
@@ -769,19 +759,17 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       la.dvec = c->dvecs[layer];
       la.d_ids = c->at<int32_t>(c->lay.true_ids);
       la.d_gates = c->at<double>(c->lay.true_gates64);
-      la.z = c->at<double>(c->lay.z);
-      la.counter = c->at<unsigned int>(c->lay.counter);
       la.ids_out = c->at<int32_t>(c->lay.la_ids);
       la.gates_out = c->at<float>(c->lay.la_gates);
       la.diag = c->at<LayerDiag>(c->lay.diag) + layer;
       la.mailbox = c->mb_look_dev;
-      ticket_look = ++c->seq;
-      la.seq = ticket_look;
+      moe_spec_ctx::arm_ids(c->mb_look, batch * k);
       la.B = batch; la.H = H; la.E = E; la.k = k;
       la.eps = cfg.rms_eps;
       la.bf16 = cfg.dtype == MOE_SPEC_BF16;
       la.spec = 1;
       la.from_normalized = cfg.q_from_normalized;
+      c->prep_route(la);
       if ((e = launch_route(la, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "lookahead routing kernel");
       c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
     }
@@ -791,8 +779,6 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   ra.r = static_cast<const float *>(r_dev);
   ra.w = c->router_w[layer];
   ra.gain = static_cast<const float *>(c->gain[layer]);
-  ra.z = c->at<double>(c->lay.z);
-  ra.counter = c->at<unsigned int>(c->lay.counter);
   ra.vec_out = c->at<float>(c->lay.s_buf);
   ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 && batch >= kMfmaMinBatch ? c->at<uint16_t>(c->lay.s_q) : nullptr;
   ra.ids_out = c->at<int32_t>(c->lay.true_ids);
@@ -804,12 +790,13 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   ra.prev_signal = cfg.diagnostics && c->have_pending ? c->at<float>(c->lay.sig) : nullptr;
   ra.user_ids = outs ? outs->true_ids : nullptr;
   ra.user_gates = outs ? outs->true_gates : nullptr;
-  ra.mailbox = exec_pred ? nullptr : c->mb_true_dev;
-  ra.seq = ticket_true;
+  ra.mailbox = true_ids_to_host ? c->mb_true_dev : nullptr;
+  if (ra.mailbox) moe_spec_ctx::arm_ids(c->mb_true, batch * k);
   ra.B = batch; ra.H = H; ra.E = E; ra.k = k;
   ra.eps = cfg.rms_eps;
   ra.bf16 = cfg.dtype == MOE_SPEC_BF16;
   ra.spec = 0;
+  c->prep_route(ra);
   if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
   c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
 
@@ -832,8 +819,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     pa.user_ids = outs ? outs->next_ids : nullptr;
     pa.user_gates = outs ? outs->next_gates : nullptr;
     pa.mailbox = prefetching ? c->mb_next_dev : nullptr;
-    ticket_next = ++c->seq;
-    pa.seq = ticket_next;
+    if (pa.mailbox) moe_spec_ctx::arm_ids(c->mb_next, batch * k);
     pa.spec = cfg.predict_signal == 1 ? 2 : 1;
     pa.from_normalized = cfg.q_from_normalized;
     if (use_est) {
@@ -844,6 +830,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       sa.user_ids = nullptr;
       sa.user_gates = nullptr;
       sa.mailbox = nullptr;
+      c->prep_route(sa);
       if ((e = launch_route(sa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "signal kernel");
       const int dm = cfg.est_latent, F = cfg.est_ffn;
       GemvArgs g{};
@@ -872,10 +859,12 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       ha.eps = c->est.ln_eps;
       ha.H = dm;
       ha.vec_out = nullptr;
+      c->prep_route(ha);
       if ((e = launch_route(ha, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "estimator head");
       c->st.hbm_bytes_algorithmic += (int64_t(dm) * H + 2 * int64_t(F) * dm + int64_t(E) * dm + dm) * wbytes +
                                      int64_t(batch) * k * H * wbytes;
     } else {
+      c->prep_route(pa);
       if ((e = launch_route(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "prediction kernel");
       c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes + int64_t(batch) * k * H * wbytes;
     }
@@ -893,7 +882,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     exec_ids_dev = c->at<int32_t>(c->lay.pend_ids[layer & 1]);
     exec_gates_dev = c->at<float>(c->lay.pend_gates[layer & 1]);
   } else {
-    int rc = fused_route ? c->wait_ids(c->mb_true, batch * k) : c->wait_mailbox(c->mb_true, ticket_true);
+    int rc = c->wait_ids(c->mb_true, batch * k);
     if (rc) return rc;
     if ((rc = c->check_ids(c->mb_true->ids, batch * k))) return rc;
     exec_union = moe_spec_ctx::sorted_union(c->mb_true->ids, batch * k);
@@ -988,7 +977,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   // --- prefetch the first wave of the predicted experts of layer l+1
   c->have_pending = do_pred;
   if (do_pred && prefetching) {
-    int rc = fused_route ? c->wait_ids(c->mb_next, batch * k) : c->wait_mailbox(c->mb_next, ticket_next);
+    int rc = c->wait_ids(c->mb_next, batch * k);
     if (rc) return rc;
     if ((rc = c->check_ids(c->mb_next->ids, batch * k))) return rc;
     c->pending_union = moe_spec_ctx::sorted_union(c->mb_next->ids, batch * k);
@@ -1019,7 +1008,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     c->look_ids[layer % 3].clear();
   }
   if (look2) {
-    int rc = c->wait_mailbox(c->mb_look, ticket_look);
+    int rc = c->wait_ids(c->mb_look, batch * k);
     if (rc) return rc;
     if ((rc = c->check_ids(c->mb_look->ids, batch * k))) return rc;
     std::vector<int> &look = c->look_ids[(layer + 2) % 3];
@@ -1104,8 +1093,6 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
     ra.r = r + size_t(t0) * H;
     ra.w = c->router_w[layer];
     ra.gain = static_cast<const float *>(c->gain[layer]);
-    ra.z = c->at<double>(c->lay.z);
-    ra.counter = c->at<unsigned int>(c->lay.counter);
     ra.vec_out = s_all + size_t(t0) * H;
     ra.vec_out_q = cfg.dtype == MOE_SPEC_BF16 ? sq_all + size_t(t0) * H : nullptr;
     ra.ids_out = ids_all + size_t(t0) * k;
@@ -1113,10 +1100,10 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
     ra.diag = c->at<LayerDiag>(c->lay.diag) + layer;
     ra.user_ids = true_ids ? true_ids + size_t(t0) * k : nullptr;
     ra.user_gates = true_gates ? true_gates + size_t(t0) * k : nullptr;
-    ra.seq = ++c->seq;
     ra.B = nb; ra.H = H; ra.E = E; ra.k = k;
     ra.eps = cfg.rms_eps;
     ra.bf16 = cfg.dtype == MOE_SPEC_BF16;
+    c->prep_route(ra);
     if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
     c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
   }
@@ -1358,8 +1345,6 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   xa.bf16 = cfg.dtype == MOE_SPEC_BF16;
   RouteArgs ra{};
   ra.r = c->at<float>(c->lay.s_buf);
-  ra.z = c->at<double>(c->lay.z);
-  ra.counter = c->at<unsigned int>(c->lay.counter);
   ra.ids_out = c->at<int32_t>(c->lay.true_ids);
   ra.gates_out = c->at<float>(c->lay.true_gates);
   ra.diag = c->at<LayerDiag>(c->lay.diag);
@@ -1431,7 +1416,7 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
       }
       else if (which == 4) { xm.pool = xa.pool; le = launch_gateup_mfma(xm, act_m, c->at<uint16_t>(c->lay.s_q), c->at<uint16_t>(c->lay.h), c->compute); }
       else if (which == 5) { xm.pool = xa.pool; le = launch_down_mfma(xm, act_m, c->at<uint16_t>(c->lay.h), c->compute); }
-      else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); le = launch_route(ra, cfg.dtype, c->compute); }
+      else { ra.w = c->router_w[l]; ra.gain = static_cast<const float *>(c->gain[l]); c->prep_route(ra); le = launch_route(ra, cfg.dtype, c->compute); }
     }
     if (pass == 1 && le == hipSuccess) le = hipEventRecord(t1, c->compute);
   }

@@ -2,15 +2,13 @@
 // layer and for the prediction of the next layer's routing from the quasi-hidden state
 // (paper: Sec. 3.1-3.3; Algorithm 1, TopK(Gate_l(X)) and GetNextExperts).
 //
-// One launch covers the whole batch: grid dimension y is the token, each token with its own
-// arrival counter, so tokens run side by side and a batch costs little more than its slowest
-// token.  Every workgroup of a token normalises the token's input row itself (a few KB from L2),
+// One launch covers the whole batch: grid dimension y is the token, so tokens run side by side and a
+// batch costs little more than its slowest token.  Every workgroup of a token normalises the token's input row itself (a few KB from L2),
 // keeps it in LDS in double precision, and one wavefront per router row reads that row once
-// with 16-byte loads.  Logits go to global memory; the last of the token's workgroups to arrive
-// (a ticket counter, no waiting) rank-sorts them in registers (keys stay in VGPRs, broadcast lane
-// by lane through scalar registers), writes ids and gates and scores the previous prediction;
-// the last token to finish posts the ids to a pinned host mailbox.  Everything that decides an
-// expert index is double precision.
+// with 16-byte loads.  Logits go to self-flagging slots in global memory; workgroup 0 of the token
+// reads them as they arrive, rank-sorts them in registers (keys stay in VGPRs, broadcast lane
+// by lane through scalar registers), writes ids and gates, scores the previous prediction and
+// writes the ids to a pinned host mailbox.  Everything that decides an expert index is double precision.
 // Layer order of the default-vector sum follows the id order (descending logit).
 #include "device_utils.h"
 #include "kernels.h"
@@ -20,25 +18,6 @@ namespace {
 
 constexpr int kMaxTokTile = 1;     // tokens a workgroup handles (one: see route_lds_bytes)
 
-// Logits travel from the workgroups that compute them to the one that sorts them through
-// device-scope atomic stores and loads, which bypass the per-XCD L2 caches' non-coherent lines.
-// The writers wait until those stores are acknowledged before they take their ticket, so no
-// device-scope fence is needed on this path: such a fence writes back and invalidates the whole
-// L2 of the XCD, and a launch of a thousand workgroups spent more time in those than in its
-// arithmetic (B = 32: 55 us with fences).
-__device__ __forceinline__ void store_coherent(double *p, double v) {
-  __hip_atomic_store(reinterpret_cast<unsigned long long *>(p),
-                     static_cast<unsigned long long>(__double_as_longlong(v)), __ATOMIC_RELAXED,
-                     __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void wait_for_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
-__device__ __forceinline__ double load_coherent(const double *p) {
-  const unsigned long long u = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
-                                                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  return __longlong_as_double(static_cast<long long>(u));
-}
-
 struct FinishShared {
   int rank[kMaxExperts];
   double top_z[kMaxTopK];
@@ -47,7 +26,8 @@ struct FinishShared {
   int hits;
 };
 
-// Top-k, gates and bookkeeping of all tokens by the whole (last) workgroup, one token at a time.
+// Top-k, gates and bookkeeping of the group's tokens by its workgroup 0, which reads the logits from their slots
+// as the other workgroups deliver them.
 template <int R>
 __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid, int b_begin, int b_end) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
@@ -62,7 +42,8 @@ __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid, int
       // with NaN are all false, ranks would collide, and slots of the top-k table would keep whatever
       // the LDS held - ids far outside [0, E) that later kernels use as row indices.  With this the
       // order (logit descending, index ascending) is total whatever the input, and ids stay in range.
-      const double zi = i < a.E ? load_coherent(a.z + size_t(b) * a.E + i) : -INFINITY;
+      double zi = -INFINITY;
+      if (i < a.E) zi = __longlong_as_double(static_cast<long long>(await64(a.slots + size_t(b) * a.E + i, a.spin_limit, a.status)));
       key[r] = zi == zi ? zi : -INFINITY;
     }
     for (int i = tid; i < kMaxExperts; i += kRouteBlock) sh.rank[i] = 0;
@@ -122,7 +103,6 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
   extern __shared__ double vec[];            // [tok_tile][H]
   __shared__ double red[kRouteBlock / kWave];
   __shared__ double red3[3][kRouteBlock / kWave];
-  __shared__ int last_flag;
   __shared__ FinishShared fin;
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
@@ -143,6 +123,11 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
     }
   }
 
+  // re-arm both sets of slots the next routing launch may use (last read by the previous launch, which has ended)
+  for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * kRouteBlock + tid; i < a.arm_count; i += gridDim.x * gridDim.y * kRouteBlock) {
+    arm64(a.arm_a + i);
+    arm64(a.arm_b + i);
+  }
   const int b_begin = blockIdx.y * a.tok_tile, b_end = min(a.B, b_begin + a.tok_tile);   // this group's tokens
   for (int b0 = b_begin; b0 < b_end; b0 += a.tok_tile) {
     const int nb = min(a.tok_tile, b_end - b0);
@@ -310,42 +295,19 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
       for (int t = 0; t < kMaxTokTile; ++t) {
         if (t < nb) {
           const double s = wave_sum(acc[t]);
-          if (lane == 0) store_coherent(a.z + size_t(b0 + t) * a.E + row, s);
+          if (lane == 0) publish64(a.slots + size_t(b0 + t) * a.E + row, s);
         }
       }
     }
     __syncthreads();                         // vec is rewritten by the next tile
   }
 
-  // Hand the group's logits to whichever of its workgroups arrives last.
-  unsigned int *arrivals = a.counter + 1 + blockIdx.y;
-  wait_for_stores();                           // this wavefront's logits have reached memory
-  __syncthreads();
-  if (tid == 0) {
-    const unsigned int ticket = __hip_atomic_fetch_add(arrivals, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    last_flag = (ticket == gridDim.x - 1);
-  }
-  __syncthreads();
-  if (!last_flag) return;
-  asm volatile("" ::: "memory");               // the logit loads below stay below
-
+  // Workgroup 0 of the group collects the logits (it waits, boundedly, only for workgroups of its own group,
+  // a few dozen at most, which fit on the device together), selects, reports and writes the ids to the host.
+  if (blockIdx.x != 0) return;
   if (a.E <= kWave) finish_tokens<1>(a, fin, tid, b_begin, b_end);
   else if (a.E <= 2 * kWave) finish_tokens<2>(a, fin, tid, b_begin, b_end);
   else finish_tokens<4>(a, fin, tid, b_begin, b_end);
-  if (a.mailbox) __threadfence_system();
-  __syncthreads();
-  if (tid == 0) {
-    __hip_atomic_store(arrivals, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    // the ids are complete when every group is: the last group to finish tells the host
-    bool all_done = true;
-    if (gridDim.y > 1) {
-      __threadfence();
-      all_done = atomicAdd(a.counter, 1u) == gridDim.y - 1;
-      if (all_done) { __threadfence(); __hip_atomic_store(a.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-    }
-    if (all_done && a.mailbox)
-      __hip_atomic_store(&a.mailbox->seq, a.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-  }
 }
 
 }  // namespace
