@@ -52,8 +52,8 @@ def parse():
     p.add_argument("--workload", default="c2_qwen3_30b_a3b")
     p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
     p.add_argument("--extra", default="auto",
-                   help="comma-separated workloads timed after the headline one, shorter (auto: c5_qwen3_b32,c1_tiny after "
-                        "the default workload, none otherwise; 'none' to skip)")
+                   help="comma-separated workloads timed after the headline one, shorter (auto: c5_qwen3_b32, c1_tiny, "
+                        "c3_gpt_oss_20b and c3_gpt_oss_20b_b8 after the default workload, none otherwise; 'none' to skip)")
     p.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU checker is timed on with all cores (0 = skip); "
                                                            "one more token is timed on a single thread")
     p.add_argument("--with-hint", action="store_true",
@@ -116,8 +116,16 @@ class Bench:
 
     def leg(self, name, counts=None, uncounted=()):
         """counts: launches of each kernel (by a substring of its name) in this leg; uncounted: kernels the leg
-        launches a data-dependent number of times."""
+        launches a data-dependent number of times (see leg_waves)."""
         self.legs.append({"leg": name, "counts": dict(counts or {}), "uncounted": list(uncounted)})
+
+    def leg_waves(self, eng):
+        """The leg just run launched its expert kernels once per cache wave: now that the count is known, record it."""
+        leg = self.legs[-1]
+        waves = eng.stats()["cache_waves"]
+        for sym in leg["uncounted"]:
+            leg["counts"][sym] = waves
+        leg["uncounted"] = []
 
     # ------------------------------------------------------------------ one workload
     def run(self, wl, K, Wm, reps, pool=None, headline=False):
@@ -192,6 +200,7 @@ class Bench:
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             after = eng.stats()
+            self.leg_waves(eng)
             return dt, {k: after[k] - before[k] for k in after}
 
         results = {m: [] for m in modes}
@@ -322,6 +331,7 @@ class Bench:
                 self.leg(f"{wl.name}/diagnostics/{name}", token_loop_counts(min(T, 16), fused_route=False), uncounted)
                 run_tokens(eng, 0, min(T, 16))
                 per = [eng.layer_diagnostics(l) for l in range(L)]
+                self.leg_waves(eng)
                 eng.close()
                 diagnostics[name] = {
                     "tokens": min(T, 16), "execution": "true experts (on-demand), so both signals see the same trajectory",
@@ -402,6 +412,7 @@ class Bench:
                         if l + 1 < L:
                             r = eng.advance(r, out, eps[t, l], wl.res_a, wl.res_b, rbuf[l & 1])
             st = eng.stats()
+            self.leg_waves(eng)
             eng.close()
             res[mode] = {"tokens": n_tokens, "transfers_issued_during_layer_call": per_layer,
                          "transfers_per_token": st["cache_misses"] / n_tokens,
@@ -465,15 +476,26 @@ def main():
 
     extra = args.extra
     if extra == "auto":
-        extra = "c5_qwen3_b32,c1_tiny" if args.workload == "c2_qwen3_30b_a3b" and not reduced else "none"
+        extra = ("c5_qwen3_b32,c1_tiny,c3_gpt_oss_20b,c3_gpt_oss_20b_b8"
+                 if args.workload == "c2_qwen3_30b_a3b" and not reduced else "none")
     legs = {}
+
+    def pool_shape(w):
+        return (w.n_layers, w.n_experts, w.expert_elems, w.dtype)
+    held = wl                                     # the workload whose pinned pool is held at the moment
     for name in [n for n in extra.split(",") if n and n != "none"]:
         xw = W.CONFIGS[name]
-        same_pool = (xw.n_layers, xw.n_experts, xw.expert_elems, xw.dtype) == (wl.n_layers, wl.n_experts, wl.expert_elems, wl.dtype)
         xk = max(4, K // 2) if xw.batch > 1 else max(K, 32)
-        res, xpool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2), pool=pool if same_pool else None)
-        if not same_pool:
+        small = xw.n_layers * xw.n_experts * xw.expert_bytes < (1 << 30)
+        if pool_shape(xw) == pool_shape(held):
+            res, pool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2), pool=pool)
+        elif small:                               # a pool this small is pinned beside the one that is held
+            res, xpool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2))
             W.free_pinned_pool(xpool)
+        else:                                     # the box cannot page-lock two large pools at once
+            W.free_pinned_pool(pool)
+            res, pool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2))
+            held = xw
         legs[name] = res
 
     if args.calibrate_copy:

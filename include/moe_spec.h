@@ -120,6 +120,8 @@ typedef struct {
   int64_t expert_launches;          /* number of such brackets */
   int64_t prefill_tokens;           /* prompt tokens through moe_spec_prefill_layer_step, summed over layers */
   int64_t predictions2, hits2;      /* lookahead = 2: recall@k of the predictions made two layers ahead */
+  int64_t cache_waves;              /* decode steps: chunks of at most S experts the executed unions were split
+                                       into; each is one cache request followed by one pass of the expert kernels */
 } moe_spec_stats_t;
 
 /* Optional per-step outputs, each dev [B, k] or NULL.  ids are by descending logit. */

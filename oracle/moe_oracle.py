@@ -274,6 +274,7 @@ class OracleStats:
     cache_hits: int = 0
     cache_misses: int = 0
     h2d_bytes: int = 0
+    cache_waves: int = 0       # chunks of at most S experts the executed unions were split into (one expert pass each)
     predictions2: int = 0      # two-layer lookahead: predictions made two layers ahead, scored like the others
     hits2: int = 0
 
@@ -497,6 +498,7 @@ class MoEOracle:
         # cache traffic: what has to be resident, in waves of at most S experts
         exec_union = sorted(set(x_ids.reshape(-1).tolist()))
         waves = chunks_of(exec_union, self.S)
+        self.stats.cache_waves += len(waves)
         prefetched = self.mode == MODE_SPECULATIVE and self.pending is not None
         for w, wave in enumerate(waves):
             if prefetched and w == 0:

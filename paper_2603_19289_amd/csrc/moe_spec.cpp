@@ -934,6 +934,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
       if ((e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
       c->close_span(sp_stall, c->compute);
     }
+    c->st.cache_waves += 1;
     TimedSpan *sp_exec = c->open_span(0, c->compute);
     TimedSpan *sp_gu = c->open_span(3, c->compute);
     if (fast_b1) {

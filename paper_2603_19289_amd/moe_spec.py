@@ -36,7 +36,8 @@ class Stats(C.Structure):
                 ("h2d_bytes", C.c_int64), ("hbm_bytes_algorithmic", C.c_int64),
                 ("copy_ms", C.c_double), ("compute_ms", C.c_double), ("stall_ms", C.c_double),
                 ("wall_ms", C.c_double), ("expert_ms", C.c_double), ("expert_launches", C.c_int64),
-                ("prefill_tokens", C.c_int64), ("predictions2", C.c_int64), ("hits2", C.c_int64)]
+                ("prefill_tokens", C.c_int64), ("predictions2", C.c_int64), ("hits2", C.c_int64),
+                ("cache_waves", C.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}

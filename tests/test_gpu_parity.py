@@ -52,7 +52,7 @@ def run_teacher_forced(wl, mode, gains="random", q_from_normalized=0, label="", 
                 worst, worst_elem = max(worst, l2), max(worst_elem, elem)
         st = eng.stats()
         for name in ("tokens", "layer_steps", "predictions", "hits", "cache_hits", "cache_misses", "h2d_bytes",
-                     "predictions2", "hits2"):
+                     "predictions2", "hits2", "cache_waves"):
             assert st[name] == getattr(orc.stats, name), (name, st[name], getattr(orc.stats, name))
     finally:
         eng.close()

@@ -151,6 +151,7 @@ def test_mode_logic_counters_and_gate_pairing(dtype, B):
     if B == 1:
         assert ond.stats.cache_hits + ond.stats.cache_misses == k * L * T
         assert spec.stats.cache_hits + spec.stats.cache_misses == k * L * T
+        assert spec.stats.cache_waves == ond.stats.cache_waves == L * T     # k <= S: one wave per layer step
 
 
 def test_router_input_is_rounded_to_bf16_only_in_bf16_mode():
@@ -172,10 +173,13 @@ def test_wave_execution_requests_when_the_union_exceeds_the_pool():
     adv = make_advance(wl, eps)
     for mode in (O.MODE_ON_DEMAND, O.MODE_SPECULATIVE):
         orc, tr = _run(model, wl, mode, x0, adv)
-        expect = 0
+        expect = waves = 0
         for t in range(wl.tokens):
             for l in range(wl.n_layers):
-                expect += len(set(tr[t][l][1].exec_ids.reshape(-1).tolist()))
+                distinct = len(set(tr[t][l][1].exec_ids.reshape(-1).tolist()))
+                expect += distinct
+                waves += -(-distinct // wl.slots)
+        assert orc.stats.cache_waves == waves > wl.tokens * wl.n_layers
         # every executed expert is requested exactly once per layer step; in speculative mode the
         # prefetch of wave 0 happens during the previous step but is still one request per expert
         assert orc.stats.cache_hits + orc.stats.cache_misses == expect
