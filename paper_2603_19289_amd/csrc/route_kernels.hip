@@ -312,7 +312,7 @@ __global__ __launch_bounds__(kRouteBlock) void route_kernel(const RouteArgs a) {
 
 }  // namespace
 
-// One token per group: the per-token chain (load, reduce, normalise, row products, ticket, sort)
+// One token per group: the per-token chain (load, reduce, normalise, row products, hand-over, sort)
 // is a sequence of dependent latencies, so tokens side by side in separate workgroups finish in
 // the time of one, while tokens one after the other in one workgroup add about 10 us each.  The
 // router rows are then read once per token, from L2 after the first.
