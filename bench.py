@@ -144,7 +144,8 @@ class Bench:
         x0_np, eps_np = W.make_inputs(wl, tokens=T)
         x0 = torch.from_numpy(x0_np).to(dev)
         eps = torch.from_numpy(eps_np).to(dev)
-        log(f"[bench] {wl.name}: pool {L * wl.n_experts * wl.expert_bytes / 1e9:.1f} GB pinned, setup {time.time() - t_setup:.1f} s")
+        log(f"[bench] {wl.name}: pool {wl.pool_bytes / 1e9:.1f} GB pinned ({wl.distinct_pool_layers} of {L} layers' expert blocks held), "
+            f"setup {time.time() - t_setup:.1f} s")
 
         # the second DMA queue pays off from a few MB per expert on; below that their set-up latency dominates
         spec_auto = "dma2" if wl.expert_bytes >= (4 << 20) else "kernel"
@@ -228,7 +229,7 @@ class Bench:
         out = {"config": {"workload": wl.name, "layers": L, "hidden": H, "experts": wl.n_experts, "top_k": wl.top_k,
                           "inter": wl.inter, "batch": B, "slots_per_layer": wl.slots, "reps": reps, "steps": K, "warmup": Wm,
                           "copy_engine": engine_names, "expert_bytes": wl.expert_bytes,
-                          "host_pool_gb": L * wl.n_experts * wl.expert_bytes / 1e9, "dtype": wl.dtype},
+                          "host_pool_gb": wl.pool_bytes / 1e9, "host_pool_layers": wl.distinct_pool_layers, "dtype": wl.dtype},
                "speculative": spec, "on_demand": ond,
                "prefetch_hint": summary("prefetch_hint") if "prefetch_hint" in modes else None,
                "speculative_lookahead2": summary("speculative_lookahead2") if "speculative_lookahead2" in modes else None,
@@ -462,8 +463,8 @@ def main():
     W = b.W
     wl = W.CONFIGS[args.workload]
     if not wl.pinnable:
-        print(f"bench.py: the pinned pool of {wl.name} ({wl.n_layers * wl.n_experts * wl.expert_bytes / 1e9:.0f} GB) exceeds what "
-              f"this box can page-lock (about 72 GB); run --workload {wl.name}_l24, the largest variant that pins.", file=sys.stderr)
+        print(f"bench.py: the pinned pool of {wl.name} ({wl.pool_bytes / 1e9:.0f} GB) exceeds what this box can "
+              f"page-lock (about 72 GB); give the workload fewer pool_layers (layers then share expert blocks).", file=sys.stderr)
         sys.exit(2)
     reduced = bool(args.layers) and args.layers != wl.n_layers
     if args.layers:

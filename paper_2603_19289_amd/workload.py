@@ -41,6 +41,8 @@ class Workload:
     w_std: float = 0.02
     d_std: float = 0.05
     per_layer_dvec: bool = False   # True: d_{l,e} identical for all e (literal per-layer reading)
+    pool_layers: int = 0           # >0: the host pool holds this many layers' expert blocks and layer l reads those
+                                   # of layer l % pool_layers (for pools larger than the box can page-lock)
 
     @property
     def elem_bytes(self) -> int:
@@ -55,8 +57,12 @@ class Workload:
         return self.expert_elems * self.elem_bytes
 
     @property
+    def distinct_pool_layers(self) -> int:
+        return min(self.pool_layers, self.n_layers) if self.pool_layers > 0 else self.n_layers
+
+    @property
     def pool_bytes(self) -> int:
-        return self.n_layers * self.n_experts * self.expert_bytes
+        return self.distinct_pool_layers * self.n_experts * self.expert_bytes
 
     @property
     def pinnable(self) -> bool:
@@ -79,10 +85,13 @@ CONFIGS: Dict[str, Workload] = {
                                _RHO, float(np.sqrt(1 - _RHO ** 2))),
     "c3_gpt_oss_20b_b8": Workload("c3_gpt_oss_20b_b8", 24, 2880, 32, 4, 2880, "bf16", 8, 256, 8, 2,
                                   _RHO, float(np.sqrt(1 - _RHO ** 2))),
+    # 32 layers x 8 experts x 352 MB = 90.2 GB of expert blocks; the GPU machines page-lock about 72 GB, so the host
+    # pool holds 24 layers' blocks (67.6 GB) and layers 24-31 read the blocks of layers 0-7.  Every layer still has
+    # its own router, default vectors, slot cache and transfers: bytes moved, kernels and cache behaviour per layer
+    # are those of 32 distinct layers; only the values of a quarter of the expert weights repeat.
     "c4_mixtral_8x7b": Workload("c4_mixtral_8x7b", 32, 4096, 8, 2, 14336, "bf16", 1, 128, 3, 3,
-                                _RHO, float(np.sqrt(1 - _RHO ** 2))),
-    # the same layers, as many of them as can be page-locked on the GPU machines (24 x 8 x 352 MB = 67.6 GB of the
-    # 90.2 GB the 32-layer workload needs): the Mixtral-shaped workload that can actually be timed
+                                _RHO, float(np.sqrt(1 - _RHO ** 2)), pool_layers=24),
+    # the same layers, 24 of them, each with its own blocks
     "c4_mixtral_8x7b_l24": Workload("c4_mixtral_8x7b_l24", 24, 4096, 8, 2, 14336, "bf16", 1, 128, 3, 3,
                                     _RHO, float(np.sqrt(1 - _RHO ** 2))),
     "c5_qwen3_b32": Workload("c5_qwen3_b32", 48, 2048, 128, 8, 768, "bf16", 32, 256, 48, 4,
@@ -194,9 +203,11 @@ def free_pinned_pool(pool) -> None:
 
 
 def alloc_pinned_pool(wl: Workload):
-    """Pinned host pool as a list of per-layer torch tensors [E, 3*H*I] in the storage dtype."""
-    return [pinned_empty(wl.n_experts * wl.expert_elems, wl.dtype).view(wl.n_experts, wl.expert_elems)
-            for _ in range(wl.n_layers)]
+    """Pinned host pool as a list of per-layer torch tensors [E, 3*H*I] in the storage dtype (entries repeat
+    when the workload's pool holds fewer layers than the model has)."""
+    held = [pinned_empty(wl.n_experts * wl.expert_elems, wl.dtype).view(wl.n_experts, wl.expert_elems)
+            for _ in range(wl.distinct_pool_layers)]
+    return [held[l % len(held)] for l in range(wl.n_layers)]
 
 
 class PoolView:
@@ -219,7 +230,7 @@ def fill_experts_gpu(wl: Workload, pool, device="cuda") -> None:
     reproduced elsewhere."""
     import torch
     g = torch.Generator(device=device)
-    for l in range(wl.n_layers):
+    for l in range(wl.distinct_pool_layers):
         g.manual_seed((wl.seed << 20) + l)
         buf = torch.empty(tuple(pool[l].shape), dtype=torch.float32, device=device)
         buf.normal_(0.0, wl.w_std, generator=g)

@@ -119,6 +119,20 @@ def test_bench_refuses_more_than_one_gpu(monkeypatch, capsys):
     assert "ONE GPU" in capsys.readouterr().err
 
 
+def test_workload_pools_fit_what_a_box_can_pin():
+    """Every registered workload must be runnable: its host pool stays under the page-locking limit, if need be by
+    holding fewer layers' expert blocks than the model has (layers then share blocks, everything else is per layer)."""
+    from paper_2603_19289_amd import workload as W
+    for wl in W.CONFIGS.values():
+        assert wl.pinnable, wl.name
+        assert 1 <= wl.distinct_pool_layers <= wl.n_layers
+        assert wl.pool_bytes == wl.distinct_pool_layers * wl.n_experts * wl.expert_bytes
+    c4 = W.CONFIGS["c4_mixtral_8x7b"]
+    assert (c4.n_layers, c4.distinct_pool_layers) == (32, 24)
+    assert c4.with_(n_layers=2).distinct_pool_layers == 2
+    assert not c4.with_(pool_layers=0).pinnable          # 90 GB: what the box refuses
+
+
 @pytest.mark.gpu
 def test_c_client_of_the_library_runs():
     """csrc/abi_demo.c uses the boundary from plain C, without Python or torch: three modes, prefill, error returns,
