@@ -53,7 +53,7 @@ def parse():
     p.add_argument("--layers", type=int, default=0, help="development only: fewer layers than the workload names")
     p.add_argument("--extra", default="auto",
                    help="comma-separated workloads timed after the headline one, shorter (auto: c5_qwen3_b32, c1_tiny, "
-                        "c3_gpt_oss_20b and c3_gpt_oss_20b_b8 after the default workload, none otherwise; 'none' to skip)")
+                        "c3_gpt_oss_20b, c3_gpt_oss_20b_b8 and c4_mixtral_8x7b after the default workload, none otherwise; 'none' to skip)")
     p.add_argument("--cpu-tokens", type=int, default=3, help="tokens the CPU checker is timed on with all cores (0 = skip); "
                                                            "one more token is timed on a single thread")
     p.add_argument("--with-hint", action="store_true",
@@ -477,7 +477,7 @@ def main():
 
     extra = args.extra
     if extra == "auto":
-        extra = ("c5_qwen3_b32,c1_tiny,c3_gpt_oss_20b,c3_gpt_oss_20b_b8"
+        extra = ("c5_qwen3_b32,c1_tiny,c3_gpt_oss_20b,c3_gpt_oss_20b_b8,c4_mixtral_8x7b"
                  if args.workload == "c2_qwen3_30b_a3b" and not reduced else "none")
     legs = {}
 
@@ -487,15 +487,16 @@ def main():
     for name in [n for n in extra.split(",") if n and n != "none"]:
         xw = W.CONFIGS[name]
         xk = max(4, K // 2) if xw.batch > 1 else max(K, 32)
-        small = xw.n_layers * xw.n_experts * xw.expert_bytes < (1 << 30)
+        small = xw.pool_bytes < (1 << 30)
+        xreps = 1 if xw.expert_bytes > (100 << 20) else min(args.reps, 2)     # a quarter of a second per token: once
         if pool_shape(xw) == pool_shape(held):
-            res, pool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2), pool=pool)
+            res, pool = b.run(xw, xk, min(Wm, 2), xreps, pool=pool)
         elif small:                               # a pool this small is pinned beside the one that is held
-            res, xpool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2))
+            res, xpool = b.run(xw, xk, min(Wm, 2), xreps)
             W.free_pinned_pool(xpool)
         else:                                     # the box cannot page-lock two large pools at once
             W.free_pinned_pool(pool)
-            res, pool = b.run(xw, xk, min(Wm, 2), min(args.reps, 2))
+            res, pool = b.run(xw, xk, min(Wm, 2), xreps)
             held = xw
         legs[name] = res
 
