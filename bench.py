@@ -485,19 +485,31 @@ def main():
         return (w.n_layers, w.n_experts, w.expert_elems, w.dtype)
     held = wl                                     # the workload whose pinned pool is held at the moment
     for name in [n for n in extra.split(",") if n and n != "none"]:
-        xw = W.CONFIGS[name]
-        xk = max(4, K // 2) if xw.batch > 1 else max(K, 32)
-        small = xw.pool_bytes < (1 << 30)
-        xreps = 1 if xw.expert_bytes > (100 << 20) else min(args.reps, 2)     # a quarter of a second per token: once
-        if pool_shape(xw) == pool_shape(held):
-            res, pool = b.run(xw, xk, min(Wm, 2), xreps, pool=pool)
-        elif small:                               # a pool this small is pinned beside the one that is held
-            res, xpool = b.run(xw, xk, min(Wm, 2), xreps)
-            W.free_pinned_pool(xpool)
-        else:                                     # the box cannot page-lock two large pools at once
-            W.free_pinned_pool(pool)
-            res, pool = b.run(xw, xk, min(Wm, 2), xreps)
-            held = xw
+        try:                                      # a further workload that fails must not cost the headline result
+            xw = W.CONFIGS[name]
+            xk = max(4, K // 2) if xw.batch > 1 else max(K, 32)
+            small = xw.pool_bytes < (1 << 30)
+            xreps = 1 if xw.expert_bytes > (100 << 20) else min(args.reps, 2)  # a quarter of a second per token: once
+            if pool is not None and pool_shape(xw) == pool_shape(held):
+                res, pool = b.run(xw, xk, min(Wm, 2), xreps, pool=pool)
+            elif small:                           # a pool this small is pinned beside the one that is held
+                res, xpool = b.run(xw, xk, min(Wm, 2), xreps)
+                W.free_pinned_pool(xpool)
+            else:                                 # the box cannot page-lock two large pools at once
+                if pool is not None:
+                    W.free_pinned_pool(pool)
+                pool, held = None, None
+                res, pool = b.run(xw, xk, min(Wm, 2), xreps)
+                held = xw
+        except Exception as exc:                  # noqa: BLE001 - reported in the line, the run goes on
+            log(f"[bench] {name} failed: {type(exc).__name__}: {exc}")
+            res = {"error": f"{type(exc).__name__}: {exc}"}
+            try:                                  # whatever the failed run still holds page-locked
+                b.torch.cuda.synchronize()
+                W.free_all_pinned()
+            except Exception:                     # noqa: BLE001
+                pass
+            pool, held = None, None
         legs[name] = res
 
     if args.calibrate_copy:
@@ -508,7 +520,8 @@ def main():
         c.copy_(a)
         torch.cuda.synchronize()
         log("[bench] calibration copy: 268435456 bytes read + 268435456 bytes written in one dispatch")
-    W.free_pinned_pool(pool)           # 58 GB of page-locked memory: unpin now, not while the process exits
+    if pool is not None:
+        W.free_pinned_pool(pool)       # tens of GB of page-locked memory: unpin now, not while the process exits
     if args.legs_file:
         with open(args.legs_file, "w") as f:
             json.dump({"legs": b.legs, "argv": sys.argv[1:]}, f)

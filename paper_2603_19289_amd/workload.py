@@ -202,6 +202,13 @@ def free_pinned_pool(pool) -> None:
             _hip_runtime.hipHostFree(ctypes.c_void_p(ptr))
 
 
+def free_all_pinned() -> None:
+    """Unpins and frees every buffer pinned_empty handed out that is still held (after a failed run)."""
+    for ptr in list(_pinned.values()):
+        _hip_runtime.hipHostFree(ctypes.c_void_p(ptr))
+    _pinned.clear()
+
+
 def alloc_pinned_pool(wl: Workload):
     """Pinned host pool as a list of per-layer torch tensors [E, 3*H*I] in the storage dtype (entries repeat
     when the workload's pool holds fewer layers than the model has)."""
