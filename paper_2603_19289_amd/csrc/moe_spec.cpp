@@ -177,11 +177,6 @@ struct moe_spec_ctx {
   std::vector<Pool> pools;
   std::vector<hipEvent_t> ready, done;
   std::vector<char> done_recorded, ready_recorded;
-  // copy_engine 2 without profiling: the DMA queues are not joined after a request; each queue that took part
-  // records its own event, [layer * copy_aux.size() + q] for the further queues, and readers wait for all of them
-  std::vector<hipEvent_t> ready_aux;
-  std::vector<char> ready_aux_recorded;
-  bool join_queues = true;
   Mailbox *mb_true = nullptr, *mb_next = nullptr, *mb_look = nullptr;       // pinned host
   Mailbox *mb_true_dev = nullptr, *mb_next_dev = nullptr, *mb_look_dev = nullptr;
   volatile unsigned int *wait_status = nullptr;         // pinned host word after the mailboxes: a kernel's bounded wait ran out
@@ -326,13 +321,6 @@ struct moe_spec_ctx {
     }
     return MOE_SPEC_OK;
   }
-  // Every copy queue waits for an event recorded on the compute stream.
-  int copy_queues_wait(hipEvent_t ev) {
-    hipError_t w = hipStreamWaitEvent(copy, ev, 0);
-    for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, ev, 0);
-    return w == hipSuccess ? MOE_SPEC_OK : hip_fail(w, "copy stream wait");
-  }
-
   // Host waits for the compute stream and every copy queue.
   hipError_t sync_streams() {
     hipError_t e = hipStreamSynchronize(compute);
@@ -340,22 +328,11 @@ struct moe_spec_ctx {
     for (hipStream_t q : copy_aux) if (e == hipSuccess) e = hipStreamSynchronize(q);
     return e;
   }
-  // A stream waits for the copies of the latest request(s) on a pool, on whichever queues they ran.
-  hipError_t wait_ready(hipStream_t s, int layer, bool main_too = true) {
-    hipError_t w = hipSuccess;
-    if (main_too && ready_recorded[layer]) w = hipStreamWaitEvent(s, ready[layer], 0);
-    for (size_t q = 0; q < copy_aux.size() && w == hipSuccess; ++q)
-      if (copy_aux[q] != s && ready_aux_recorded[size_t(layer) * copy_aux.size() + q])
-        w = hipStreamWaitEvent(s, ready_aux[size_t(layer) * copy_aux.size() + q], 0);
-    return w;
-  }
-  // Every copy queue behind the previous request on this pool, whichever queues that ran on (a queue is behind
-  // its own earlier copies anyway): the slots may be reused before any kernel ran, e.g. by a true request right
-  // after a mispredicted prefetch.
-  hipError_t queues_behind_previous_request(int layer) {
-    hipError_t w = wait_ready(copy, layer, false);
-    for (hipStream_t q : copy_aux) if (w == hipSuccess) w = wait_ready(q, layer);
-    return w;
+  // Every copy queue waits for an event recorded on the compute stream.
+  int copy_queues_wait(hipEvent_t ev) {
+    hipError_t w = hipStreamWaitEvent(copy, ev, 0);
+    for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, ev, 0);
+    return w == hipSuccess ? MOE_SPEC_OK : hip_fail(w, "copy stream wait");
   }
 
   // Cache request for at most S experts (ascending ids): hits are stamped, each miss takes the
@@ -394,9 +371,13 @@ struct moe_spec_ctx {
           for (hipStream_t q : copy_aux) if (w == hipSuccess) w = hipStreamWaitEvent(q, done[layer], 0);
           if (w != hipSuccess) return hip_fail(w, "copy stream wait");
         }
-        if (!copy_aux.empty()) {
-          hipError_t w = queues_behind_previous_request(layer);
-          if (w != hipSuccess) return hip_fail(w, "copy queue wait");
+        if (ready_recorded[layer]) {
+          // further queues: also behind the previous request on this pool (its slots may be reused
+          // by this one before any kernel ran, e.g. a true request right after a mispredicted prefetch)
+          for (hipStream_t q : copy_aux) {
+            hipError_t w = hipStreamWaitEvent(q, ready[layer], 0);
+            if (w != hipSuccess) return hip_fail(w, "copy queue wait");
+          }
         }
         span = open_span(1, copy);
       }
@@ -410,26 +391,14 @@ struct moe_spec_ctx {
       st.cache_misses += 1;
       st.h2d_bytes += int64_t(expert_bytes);
     }
-    if (copies > 0 && (join_queues || copy_aux.empty())) {
-      // the request is complete when every queue is: the copy stream waits for the others
+    if (copies > 0) {                            // the request is complete when every queue is
       if (int rc = copy_join(cl)) return rc;
+    }
+    if (copies > 0) {
       close_span(span, copy);
       hipError_t r = hipEventRecord(ready[layer], copy);
       if (r != hipSuccess) return hip_fail(r, "record ready event");
       ready_recorded[layer] = 1;
-    } else if (copies > 0) {
-      // the queues run on independently (a join costs the waiting DMA queue tens of microseconds per request):
-      // each queue that received blocks records its own event
-      hipError_t r = hipEventRecord(ready[layer], copy);
-      ready_recorded[layer] = 1;
-      const size_t nq = 1 + copy_aux.size();
-      for (size_t q = 1; q < nq && r == hipSuccess; ++q) {
-        if (size_t(copies) > q) {                 // block `index` went to queue index % nq
-          r = hipEventRecord(ready_aux[size_t(layer) * copy_aux.size() + q - 1], copy_aux[q - 1]);
-          ready_aux_recorded[size_t(layer) * copy_aux.size() + q - 1] = 1;
-        }
-      }
-      if (r != hipSuccess) return hip_fail(r, "record ready event");
     }
     for (int e : experts) {
       act->expert[act->n] = int16_t(e);
@@ -571,11 +540,6 @@ int moe_spec_create(const moe_spec_config *cfg, moe_spec_ctx **out) {
       if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
       c->aux_done.push_back(ev);
     }
-    c->join_queues = cfg->profile != 0;          // the copy spans of a profiled context end at the join
-    c->ready_aux.assign(size_t(L) * c->copy_aux.size(), nullptr);
-    c->ready_aux_recorded.assign(c->ready_aux.size(), 0);
-    for (hipEvent_t &ev : c->ready_aux)
-      if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) return bail(e, "event");
   }
   void *mb = nullptr;
   // fine-grained (coherent) pinned memory: device stores become visible to the spinning host
@@ -613,7 +577,6 @@ void moe_spec_destroy(moe_spec_ctx *c) {
   }
   for (hipStream_t q : c->copy_aux) (void)hipStreamDestroy(q);
   for (hipEvent_t ev : c->aux_done) (void)hipEventDestroy(ev);
-  for (hipEvent_t ev : c->ready_aux) if (ev) (void)hipEventDestroy(ev);
   for (int h = 0; h < 2; ++h) {
     if (c->pf_ready[h]) (void)hipEventDestroy(c->pf_ready[h]);
     if (c->pf_done[h]) (void)hipEventDestroy(c->pf_done[h]);
@@ -974,7 +937,7 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
     }
     if (need_wait) {
       TimedSpan *sp_stall = c->open_span(2, c->compute);
-      if ((e = c->wait_ready(c->compute, layer)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
+      if ((e = hipStreamWaitEvent(c->compute, c->ready[layer], 0)) != hipSuccess) return c->hip_fail(e, "compute stream wait");
       c->close_span(sp_stall, c->compute);
     }
     c->st.cache_waves += 1;
@@ -1165,8 +1128,10 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
   std::fill(p.where.begin(), p.where.end(), -1);
   p.clock = 0;
   if (c->done_recorded[layer]) { int rc = c->copy_queues_wait(c->done[layer]); if (rc) return rc; }
-  if (!c->copy_aux.empty() && (e = c->queues_behind_previous_request(layer)) != hipSuccess)
-    return c->hip_fail(e, "copy queue wait");
+  if (c->ready_recorded[layer]) {
+    for (hipStream_t q : c->copy_aux)
+      if ((e = hipStreamWaitEvent(q, c->ready[layer], 0)) != hipSuccess) return c->hip_fail(e, "copy queue wait");
+  }
 
   // --- stream every expert through the two halves of the pool
   for (int e0 = 0, g = 0; e0 < E; e0 += group, ++g) {
