@@ -430,9 +430,11 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
     if (GATEUP) { st.w1[0] = load_bf16x8(p1 + kk, v0); st.w1[1] = load_bf16x8(p1 + kk + 8, v1); }
   };
   MfmaStep<GATEUP, NT> even, odd;              // the loads of one step are in flight during the other's MFMAs
-  // down projection: the first weights are on their way while the token list is built (measured: 6 % faster
-  // there, 7 % slower in the gate/up kernel, which has twice the weight registers per step)
-  if (!GATEUP) fetch_w(k_begin, even);
+  // down projection with one token tile: the first weights are on their way while the token list is built
+  // (measured: 6 % faster there; 7 % slower in the gate/up kernel, which has twice the weight registers per step,
+  // and 20 % slower with two token tiles, as in prefill)
+  constexpr bool kEarlyWeights = !GATEUP && NT == 1;
+  if (kEarlyWeights) fetch_w(k_begin, even);
 
   int n;
   if (a.pos_list) {
@@ -487,8 +489,8 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
       }
     }
   };
-  if (GATEUP) fetch(k_begin, even);
-  else fetch_x(k_begin, even);
+  if (kEarlyWeights) fetch_x(k_begin, even);
+  else fetch(k_begin, even);
   for (int k0 = k_begin; k0 < k_end; k0 += 128) {
     fetch(k0 + 64, odd);
     multiply(even);
