@@ -430,10 +430,10 @@ __global__ __launch_bounds__(kBlock) void expert_mfma_kernel(const ExpertArgs a,
     if (GATEUP) { st.w1[0] = load_bf16x8(p1 + kk, v0); st.w1[1] = load_bf16x8(p1 + kk + 8, v1); }
   };
   MfmaStep<GATEUP, NT> even, odd;              // the loads of one step are in flight during the other's MFMAs
-  // down projection with one token tile: the first weights are on their way while the token list is built
-  // (measured: 6 % faster there; 7 % slower in the gate/up kernel, which has twice the weight registers per step,
-  // and 20 % slower with two token tiles, as in prefill)
-  constexpr bool kEarlyWeights = !GATEUP && NT == 1;
+  // down projection with up to two token tiles: the first weights are on their way while the token list is
+  // built (measured: 6 % faster there; 7 % slower in the gate/up kernel, which has twice the weight registers
+  // per step, and 20 % slower with four token tiles, as in prefill)
+  constexpr bool kEarlyWeights = !GATEUP && NT <= 2;
   if (kEarlyWeights) fetch_w(k_begin, even);
 
   int n;
