@@ -206,3 +206,42 @@ def test_crafted_ties_pick_the_lower_index():
                 np.testing.assert_array_equal(ids["true_ids"].cpu().numpy(), trace[t][l][1].true_ids)
     finally:
         eng.close()
+
+
+@pytest.mark.parametrize("seed", [11, 12])
+def test_randomised_configurations(seed):
+    """Sixty seeded draws per seed of everything a configuration can vary within the documented limits (sizes that
+    are no multiple of a tile, one expert, k = E, S = k, batches up to 64, every mode, copy engine and reading of
+    q_l, the two-layer lookahead), each teacher-forced against the checker for a few tokens."""
+    from paper_2603_19289_amd import moe_spec as M   # noqa: F401
+    rng = np.random.default_rng(seed)
+    hiddens = [8, 16, 24, 40, 64, 72, 136, 256, 520, 1000, 1024, 2056]
+    inters = [8, 16, 40, 48, 104, 256, 520]
+    batches = [1, 1, 1, 2, 3, 5, 8, 17, 33, 64]
+    for case in range(60):
+        H, I = int(rng.choice(hiddens)), int(rng.choice(inters))
+        E = int(rng.integers(1, 65)) if rng.random() < 0.85 else int(rng.integers(65, 257))
+        k = int(rng.integers(1, min(E, 16) + 1))
+        S = int(rng.integers(k, E + 3))
+        B = int(rng.choice(batches))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        mode = list(MODES)[int(rng.integers(0, 3))]
+        L, T = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        while L * E * 3 * H * I > 1.2e8:             # the pool is drawn on the CPU
+            if I > 48:
+                I = 48
+            elif H > 136:
+                H = 136
+            else:
+                E = max(k, E // 2)
+                S = max(k, min(S, E + 2))
+        while B * k * L * T * 3 * H * I > 6e8 and B > 1:   # the checker's work
+            B = max(1, B // 2)
+        look = mode != "on_demand" and L >= 3 and rng.random() < 0.3
+        wl = small_workload(name=f"draw{seed}_{case}", n_layers=L, hidden=H, n_experts=E, top_k=k, inter=I, dtype=dtype,
+                            batch=B, tokens=T, slots=S, seed=1000 * seed + case)
+        kw = dict(copy_engine=int(rng.integers(0, 3)))
+        if look:
+            kw["lookahead"] = 2
+        run_teacher_forced(wl, MODES[mode], q_from_normalized=int(rng.random() < 0.2),
+                           oracle_kw=dict(lookahead=2) if look else None, **kw)
