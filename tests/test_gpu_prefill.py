@@ -186,3 +186,33 @@ def test_prefill_argument_and_state_errors():
         assert ei.value.code == M.ESTATE
     finally:
         eng.close()
+
+
+def test_prefill_randomised_configurations():
+    """Eighty seeded draws of layer sizes, expert counts, pool sizes, prompt lengths, micro-batches, dtypes and copy
+    engines within the documented limits, each against the checker."""
+    rng = np.random.default_rng(21)
+    hiddens = [8, 16, 24, 40, 64, 72, 136, 256, 520, 1000]
+    inters = [8, 16, 40, 48, 104, 256]
+    for case in range(80):
+        H, I = int(rng.choice(hiddens)), int(rng.choice(inters))
+        E = int(rng.integers(1, 49)) if rng.random() < 0.9 else int(rng.integers(49, 200))
+        k = int(rng.integers(1, min(E, 16) + 1))
+        S = int(rng.integers(k, E + 3))
+        P = int(rng.choice([1, 2, 3, 7, 16, 17, 33, 64, 65, 100, 130, 257]))
+        micro = int(rng.choice([1, 2, 3, 8, 16, 31, 64]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        L = int(rng.integers(1, 4))
+        while L * E * 3 * H * I > 1.0e8:             # the pool is drawn on the CPU
+            if I > 48:
+                I = 48
+            elif H > 136:
+                H = 136
+            else:
+                E = max(k, E // 2)
+                S = max(k, min(S, E + 2))
+        while P * k * L * 3 * H * I > 1.5e9 and P > 1:   # the checker's work
+            P = max(1, P // 2)
+        wl = small_workload(name=f"pdraw{case}", n_layers=L, hidden=H, n_experts=E, top_k=k, inter=I, dtype=dtype,
+                            batch=1, tokens=1, slots=S, seed=5000 + case)
+        run_prefill(wl, P=P, max_batch=micro, label=f"draw {case}", copy_engine=int(rng.integers(0, 3)))
