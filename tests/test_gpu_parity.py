@@ -245,3 +245,43 @@ def test_randomised_configurations(seed):
             kw["lookahead"] = 2
         run_teacher_forced(wl, MODES[mode], q_from_normalized=int(rng.random() < 0.2),
                            oracle_kw=dict(lookahead=2) if look else None, **kw)
+
+
+def test_randomised_configurations_of_the_one_routing_kernel_paths():
+    """Sixty seeded draws through the paths that keep one kernel per routing: estimator at a random subset of layers
+    (Est-PF / Hybrid-PF), the baseline signal, per-layer diagnostics; sizes, batches, modes and copy engines vary."""
+    rng = np.random.default_rng(31)
+    for case in range(60):
+        m, n = int(rng.choice([1, 2, 3, 4])), int(rng.choice([1, 2, 3]))
+        H = int(rng.choice([8, 16, 24, 40, 88, 128, 264])) * m          # latent size H/m, a multiple of 8
+        I = int(rng.choice([8, 16, 40, 48, 104]))
+        E = int(rng.integers(1, 65)) if rng.random() < 0.85 else int(rng.integers(65, 257))
+        k = int(rng.integers(1, min(E, 16) + 1))
+        S = int(rng.integers(k, E + 3))
+        B = int(rng.choice([1, 1, 2, 3, 5, 8, 17, 33, 64]))
+        dtype = "bf16" if rng.random() < 0.7 else "f32"
+        mode = list(MODES)[int(rng.integers(0, 3))]
+        L, T = int(rng.integers(2, 6)), int(rng.integers(1, 4))
+        while L * E * 3 * H * I > 1.0e8:             # the pool is drawn on the CPU
+            if I > 16:
+                I = 16
+            else:
+                E = max(k, E // 2)
+                S = max(k, min(S, E + 2))
+        while B * k * L * T * 3 * H * I > 6e8 and B > 1:   # the checker's work
+            B = max(1, B // 2)
+        wl = small_workload(name=f"odraw{case}", n_layers=L, hidden=H, n_experts=E, top_k=k, inter=I, dtype=dtype,
+                            batch=B, tokens=T, slots=S, seed=9000 + case)
+        kind = int(rng.integers(0, 3))
+        kw, okw = dict(copy_engine=int(rng.integers(0, 3))), {}
+        if kind == 0:
+            est = W.make_estimator(wl, m=m, n=n)
+            use = [l for l in range(L) if rng.random() < 0.6] or [0]
+            kw.update(estimator=est, estimator_layers=use)
+            okw.update(estimator=O.Estimator(**est), estimator_layers=use)
+        elif kind == 1:
+            kw.update(predict_signal=1)
+            okw.update(predict_signal=1)
+        else:
+            kw.update(diagnostics=1)
+        run_teacher_forced(wl, MODES[mode], oracle_kw=okw, **kw)
