@@ -14,8 +14,19 @@ from paper_2603_19289_amd import workload as W
 # pre-image where the checker rounds from float64, so now and then one h_i lands on the neighbouring
 # bf16 value (2^-8 relative) and moves every output element by g * W_down[row, i] * ulp(h_i).  The
 # constants are four to five times the worst values the GPU tests print (2.0e-6 and 2.5e-3).
+# An output element is a sum of k*I terms, its row's RMS about sqrt(k*I) times one term's spread; one flipped
+# h_i moves one term by up to 2^-7 of itself, and a term can be a few times the spread, so a single flip shows as
+# up to about 0.1 / sqrt(k*I) of the RMS: below 1e-2 from some 250 terms on (every benchmark shape has thousands),
+# above it for the tiny layers the randomised tests draw (k*I = 24: 1.1e-2 seen, reproduced to the last bit by a
+# float32 emulation of the kernel's SwiGLU step).  elem_tol widens the bound for those and only for those.
 L2_TOL = {"f32": 1e-5, "bf16": 2e-2}
 ELEM_TOL = {"f32": 1e-5, "bf16": 1e-2}
+
+
+def elem_tol(dtype, terms=None):
+    if dtype != "bf16" or not terms:
+        return ELEM_TOL[dtype]
+    return max(ELEM_TOL[dtype], 0.16 / float(np.sqrt(terms)))
 
 
 def output_errors(got, want):
@@ -28,10 +39,11 @@ def output_errors(got, want):
     return float(l2.max()), float(elem.max())
 
 
-def check_output(got, want, dtype, where=""):
+def check_output(got, want, dtype, where="", terms=None):
+    """terms: k * I, the number of products an output element sums (see elem_tol)."""
     l2, elem = output_errors(got, want)
     assert l2 <= L2_TOL[dtype], f"{where}: relative L2 error {l2:.3e}"
-    assert elem <= ELEM_TOL[dtype], f"{where}: an element is off by {elem:.3e} of its row's RMS"
+    assert elem <= elem_tol(dtype, terms), f"{where}: an element is off by {elem:.3e} of its row's RMS"
     return l2, elem
 
 
