@@ -336,3 +336,95 @@ def test_a_wait_that_runs_out_is_reported_and_reset_recovers():
         assert eng.stats()["hits"] == orc.stats.hits
     finally:
         eng.close()
+
+
+def test_random_call_sequences_leave_a_working_context():
+    """Forty seeded contexts, each put through 10 to 60 random calls, valid and invalid (steps in and out of order,
+    oversized batches, null pointers, resets and statistics in the middle of a token, timing and prefill calls at the
+    wrong moment, both entry points of the layer step): invalid calls must be refused with EINVAL / ESTATE, and
+    afterwards a clean token through the context must equal, bit for bit, the same token through a context that saw
+    none of it."""
+    rng = np.random.default_rng(61)
+    modes = [M.MODE_ON_DEMAND, M.MODE_SPECULATIVE, M.MODE_PREFETCH_HINT]
+
+    def clean_token(eng, wl, x, static):
+        eng.reset()
+        eng.begin_token()
+        outs, r = [], x
+        for l in range(wl.n_layers):
+            out, _ = eng.layer_step(l, r, static_scratch=static)
+            torch.cuda.synchronize()
+            outs.append(out.clone())
+            r = (r + out).contiguous()
+        return outs
+
+    for case in range(40):
+        L, E = int(rng.integers(2, 6)), int(rng.integers(2, 24))
+        k = int(rng.integers(1, min(E, 6) + 1))
+        S, Bmax = int(rng.integers(k, E + 1)), int(rng.choice([1, 2, 5, 16]))
+        mode = modes[int(rng.integers(0, 3))]
+        wl = small_workload(name=f"calls{case}", n_layers=L, hidden=int(rng.choice([16, 64, 264])), n_experts=E, top_k=k,
+                            inter=int(rng.choice([8, 40, 104])), dtype="bf16" if rng.random() < 0.6 else "f32",
+                            batch=Bmax, tokens=1, slots=S, seed=6100 + case)
+        look = 2 if (mode != M.MODE_ON_DEMAND and L >= 3 and rng.random() < 0.3) else 0
+        kw = dict(copy_engine=int(rng.integers(0, 3)), lookahead=look, max_prefill_tokens=int(rng.choice([0, 0, 32])))
+        res, ex, _ = build(wl, "random")
+        eng, ref = _engine(wl, mode, res, ex, **kw), _engine(wl, mode, res, ex, **kw)
+        g = torch.Generator(device="cuda").manual_seed(case)
+        is_open, nxt, batch = False, 0, 0
+        try:
+            for _ in range(int(rng.integers(10, 60))):
+                op = rng.choice(["begin", "step", "step", "step", "wrong_layer", "bad_batch", "reset", "stats", "time",
+                                 "prefill", "null"])
+                must_fail = must_pass = False
+                try:
+                    if op == "begin":
+                        must_pass = True
+                        eng.begin_token()
+                        is_open, nxt = True, 0
+                    elif op == "step":
+                        B = int(rng.integers(1, Bmax + 1)) if nxt == 0 else batch
+                        must_pass, must_fail = is_open, not is_open
+                        r = torch.randn((B, wl.hidden), generator=g, device="cuda")
+                        eng.layer_step(nxt if is_open else 0, r, static_scratch=bool(rng.random() < 0.5))
+                        batch, nxt = B, nxt + 1
+                        is_open = nxt < L
+                    elif op == "wrong_layer":
+                        must_fail = True
+                        r = torch.randn((max(batch, 1), wl.hidden), generator=g, device="cuda")
+                        eng.layer_step(nxt + 1, r)
+                    elif op == "bad_batch":
+                        must_fail = True
+                        eng.layer_step(nxt, torch.randn((Bmax + 1, wl.hidden), generator=g, device="cuda"))
+                    elif op == "reset":
+                        must_pass = True
+                        eng.reset()
+                        is_open, nxt = False, 0
+                    elif op == "stats":
+                        must_pass = True
+                        eng.stats()
+                    elif op == "time":
+                        must_fail = is_open
+                        eng.time_kernel(int(rng.choice([0, 1, 2, 3, 9])), 3)
+                    elif op == "prefill":
+                        must_fail = kw["max_prefill_tokens"] == 0 or is_open
+                        must_pass = not must_fail
+                        r = torch.randn((int(rng.integers(1, 33)), wl.hidden), generator=g, device="cuda")
+                        for l in range(L):
+                            eng.prefill_layer_step(l, r)
+                    else:
+                        must_fail = True
+                        M.moe_spec_layer_step(eng.ctx, nxt, 0, 1, 0)
+                    assert not must_fail, (case, op)
+                except M.MoeSpecError as e:
+                    assert e.code in (M.EINVAL, M.ESTATE), (case, op, e)
+                    assert not must_pass, (case, op, e)
+            torch.cuda.synchronize()
+            x = torch.randn((Bmax, wl.hidden), generator=torch.Generator(device="cuda").manual_seed(999), device="cuda")
+            for static in (False, True):
+                a, b = clean_token(eng, wl, x, static), clean_token(ref, wl, x, static)
+                for l in range(L):
+                    assert torch.equal(a[l].view(torch.int32), b[l].view(torch.int32)), (case, static, l)
+        finally:
+            eng.close()
+            ref.close()
