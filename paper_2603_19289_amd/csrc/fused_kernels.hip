@@ -208,9 +208,10 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
   // ---- s_l = LN_l(r_l)
   {
     double ss = 0.0;
+    double v0[VN];                               // this thread's first columns stay in registers until they are final
     if (c0 < H) {
 #pragma unroll
-      for (int x = 0; x < VN; ++x) { vec[c0 + x] = double(r0[x]) * double(g0[x]); ss += double(r0[x]) * double(r0[x]); }
+      for (int x = 0; x < VN; ++x) { v0[x] = double(r0[x]) * double(g0[x]); ss += double(r0[x]) * double(r0[x]); }
     }
     for (int c = c0 + kBlock * VN; c < H; c += kBlock * VN) {
 #pragma unroll
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     for (int c = c0; c < H; c += kBlock * VN) {
 #pragma unroll
       for (int x = 0; x < VN; ++x) {
-        double n = vec[c + x] * inv;
+        double n = (c == c0 ? v0[x] : vec[c + x]) * inv;
         if (a.bf16) n = round_to_bf16_fast(n);
         vec[c + x] = n;
       }
@@ -353,6 +354,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
   {
     const double inv_denom = 1.0 / denom;
     double ss = 0.0;
+    double q0[VN];                               // as in the first norm: the first columns stay in registers
     for (int c = c0; c < H; c += kBlock * VN) {
       const bool first = c == c0;
       double u[VN];
@@ -404,7 +406,8 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
 #pragma unroll
       for (int x = 0; x < VN; ++x) {
         const double ux = u[x] + d[x];
-        vec[c + x] = ux * double(gf[x]);
+        if (first) q0[x] = ux * double(gf[x]);
+        else vec[c + x] = ux * double(gf[x]);
         ss += ux * ux;
       }
     }
@@ -414,7 +417,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     for (int c = c0; c < H; c += kBlock * VN) {
 #pragma unroll
       for (int x = 0; x < VN; ++x) {
-        double n = vec[c + x] * inv;
+        double n = (c == c0 ? q0[x] : vec[c + x]) * inv;
         if (a.bf16) n = round_to_bf16_fast(n);
         vec[c + x] = n;
       }
