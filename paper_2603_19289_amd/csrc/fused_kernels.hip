@@ -159,7 +159,12 @@ __device__ __forceinline__ double select_gates(int k, SelectShared &sel, int tid
 template <typename WT, int SPLIT, int NCH, int ROWS>
 __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs a) {
   static_assert(ROWS == 1 || SPLIT == 1, "several rows per wavefront only with one wavefront per row");
-  extern __shared__ double vec[];              // [H] the router input being built, double precision
+  // The router input being built, double precision, H values.  Threads own groups of VN consecutive columns (in
+  // the norms: group tid, tid + 256, ...; in the products: the groups of the wavefront's chunks); column x of
+  // group o lives at word x * G + o, so that the lanes of a wavefront, which hold consecutive groups, touch
+  // consecutive words whatever x is (with the columns in their natural order every access of a wavefront fell
+  // on a few banks)
+  extern __shared__ double vec_lds[];
   __shared__ RouteShared sh;
   using P = Packed<WT>;
   using Raw = typename P::Raw;
@@ -169,6 +174,8 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
   const int wg = blockIdx.x, b = blockIdx.y;
   const int H = a.H, E = a.E, k = a.k;
+  const int G = H / VN;                        // column groups (H is a multiple of 8)
+#define V(c, x) vec_lds[(x) * G + (c) / VN]
   const int row = wg * RPW + wave / SPLIT * ROWS, part = wave % SPLIT;   // this wavefront's (first) row
   const bool pred = a.w_next != nullptr;
   const WT *wt = static_cast<const WT *>(a.w_true);
@@ -218,8 +225,8 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
       for (int x = 0; x < VN; x += 4) {
         const float4 f = *reinterpret_cast<const float4 *>(rrow + c + x);
         const float4 g = *reinterpret_cast<const float4 *>(a.gain_true + c + x);
-        vec[c + x] = double(f.x) * double(g.x); vec[c + x + 1] = double(f.y) * double(g.y);
-        vec[c + x + 2] = double(f.z) * double(g.z); vec[c + x + 3] = double(f.w) * double(g.w);
+        V(c, x) = double(f.x) * double(g.x); V(c, x + 1) = double(f.y) * double(g.y);
+        V(c, x + 2) = double(f.z) * double(g.z); V(c, x + 3) = double(f.w) * double(g.w);
         ss += double(f.x) * double(f.x) + double(f.y) * double(f.y) + double(f.z) * double(f.z) + double(f.w) * double(f.w);
       }
     }
@@ -228,20 +235,20 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     for (int c = c0; c < H; c += kBlock * VN) {
 #pragma unroll
       for (int x = 0; x < VN; ++x) {
-        double n = (c == c0 ? v0[x] : vec[c + x]) * inv;
+        double n = (c == c0 ? v0[x] : V(c, x)) * inv;
         if (a.bf16) n = round_to_bf16_fast(n);
-        vec[c + x] = n;
+        V(c, x) = n;
       }
       if (wg == 0) {                             // s_l for the expert kernels, 16 bytes per store
 #pragma unroll
         for (int x = 0; x < VN; x += 4)
           *reinterpret_cast<float4 *>(a.s_out + size_t(b) * H + c + x) =
-              make_float4(float(vec[c + x]), float(vec[c + x + 1]), float(vec[c + x + 2]), float(vec[c + x + 3]));
+              make_float4(float(V(c, x)), float(V(c, x + 1)), float(V(c, x + 2)), float(V(c, x + 3)));
         if (a.s_out_q) {
 #pragma unroll
           for (int x = 0; x < VN; x += 2)
             *reinterpret_cast<uint32_t *>(a.s_out_q + size_t(b) * H + c + x) =
-                (__float_as_uint(float(vec[c + x])) >> 16) | (__float_as_uint(float(vec[c + x + 1])) & 0xffff0000u);
+                (__float_as_uint(float(V(c, x))) >> 16) | (__float_as_uint(float(V(c, x + 1))) & 0xffff0000u);
         }
       }
     }
@@ -259,7 +266,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
         float wf[VN];
         P::unpack(w[ch], wf);
 #pragma unroll
-        for (int x = 0; x < VN; ++x) acc += double(wf[x]) * vec[c + x];
+        for (int x = 0; x < VN; ++x) acc += double(wf[x]) * V(c, x);
       }
     }
     return wave_sum(acc);
@@ -360,7 +367,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
       double u[VN];
       if (a.from_normalized) {
 #pragma unroll
-        for (int x = 0; x < VN; ++x) u[x] = vec[c + x];
+        for (int x = 0; x < VN; ++x) u[x] = V(c, x);
       } else if (first) {
 #pragma unroll
         for (int x = 0; x < VN; ++x) u[x] = r0[x];
@@ -407,7 +414,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
       for (int x = 0; x < VN; ++x) {
         const double ux = u[x] + d[x];
         if (first) q0[x] = ux * double(gf[x]);
-        else vec[c + x] = ux * double(gf[x]);
+        else V(c, x) = ux * double(gf[x]);
         ss += ux * ux;
       }
     }
@@ -417,9 +424,9 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     for (int c = c0; c < H; c += kBlock * VN) {
 #pragma unroll
       for (int x = 0; x < VN; ++x) {
-        double n = (c == c0 ? q0[x] : vec[c + x]) * inv;
+        double n = (c == c0 ? q0[x] : V(c, x)) * inv;
         if (a.bf16) n = round_to_bf16_fast(n);
-        vec[c + x] = n;
+        V(c, x) = n;
       }
     }
     __syncthreads();
@@ -444,6 +451,7 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
     if (a.user_next_gates) a.user_next_gates[o] = g;
   }
   STAGE(11);
+#undef V
 }
 
 // ---------------------------------------------------------------------------------------------
