@@ -1334,6 +1334,21 @@ int moe_spec_time_kernel(moe_spec_ctx *c, int which, int reps, double *ms_per_la
   for (int j = 0; j < k; ++j) { ids[j] = j; act.expert[j] = int16_t(j); act.slot[j] = int16_t(j); }
   if ((e = hipMemcpyAsync(c->arena + c->lay.bench_ids, ids, size_t(k) * 4, hipMemcpyHostToDevice, c->compute)) != hipSuccess)
     return c->hip_fail(e, "upload ids");
+  // The activations the launches read: a bell-shaped draw per element (sum of four uniforms), so that logits are
+  // distinct as they are in a decode step (equal logits, as zeros would give, send the top-k through its
+  // tie-breaking path on every comparison).
+  {
+    std::vector<float> rin(size_t(cfg.max_batch) * H);
+    uint32_t state = 0x9e3779b9u;
+    for (float &v : rin) {
+      float acc = 0.f;
+      for (int u = 0; u < 4; ++u) { state = state * 1664525u + 1013904223u; acc += float(state >> 8) * (1.0f / 16777216.0f); }
+      v = (acc - 2.0f) * 1.7320508f;
+    }
+    if ((e = hipMemcpyAsync(c->arena + c->lay.s_buf, rin.data(), rin.size() * 4, hipMemcpyHostToDevice, c->compute)) != hipSuccess ||
+        (e = hipStreamSynchronize(c->compute)) != hipSuccess)
+      return c->hip_fail(e, "upload activations");
+  }
   hipEvent_t t0 = nullptr, t1 = nullptr;
   if ((e = hipEventCreate(&t0)) != hipSuccess) return c->hip_fail(e, "event");
   if ((e = hipEventCreate(&t1)) != hipSuccess) { (void)hipEventDestroy(t0); return c->hip_fail(e, "event"); }
