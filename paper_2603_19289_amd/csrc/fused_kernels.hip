@@ -34,6 +34,7 @@ constexpr int kWaves = kBlock / kWave;
 // Routing
 
 struct SelectShared {
+  unsigned long long keys[kMaxExperts];   // the token's logits as order-preserving integers
   int cnt[kWaves][kMaxExperts];   // partial rank counts of the four wavefronts
   double top_z[kMaxTopK];
   double top_e[kMaxTopK];
@@ -86,18 +87,21 @@ __device__ void select_ids(const RoutePairArgs &a, int stage, const unsigned lon
                            SelectShared &sel, int tid) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int kSrcPerWave = kWave / kWaves;
+  // thread i waits for logit i (one look at every slot per workgroup, not one per wavefront) and shares it
+  // through LDS; then every wavefront holds all candidates in registers
+  static_assert(kMaxExperts == kBlock, "one thread per candidate");
+  unsigned long long mine = 0ull;                // padding ranks below every logit, minus infinity included
+  if (tid < E) {
+    const double zi = __longlong_as_double(static_cast<long long>(await64(slots + tid, a.spin_limit, a.status)));
+    // a logit that is not a number (an empty slot after a wait that ran out) sorts as minus infinity: the
+    // order stays total whatever the input, so the k ids are distinct and inside [0, E)
+    mine = sortable(zi == zi ? zi : -INFINITY);
+  }
+  sel.keys[tid] = mine;
+  __syncthreads();
   unsigned long long key[R];
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
-    const int i = r * kWave + lane;
-    key[r] = 0ull;                               // padding ranks below every logit, minus infinity included
-    if (i < E) {
-      const double zi = __longlong_as_double(static_cast<long long>(await64(slots + i, a.spin_limit, a.status)));
-      // a logit that is not a number (an empty slot after a wait that ran out) sorts as minus infinity: the
-      // order stays total whatever the input, so the k ids are distinct and inside [0, E)
-      key[r] = sortable(zi == zi ? zi : -INFINITY);
-    }
-  }
+  for (int r = 0; r < R; ++r) key[r] = sel.keys[r * kWave + lane];
   STAGE(stage);
   int cnt[R];
 #pragma unroll
