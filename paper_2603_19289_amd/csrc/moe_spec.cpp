@@ -1090,12 +1090,41 @@ int moe_spec_prefill_layer_step(moe_spec_ctx *c, int layer, const void *r_dev, i
   float *gates_all = c->at<float>(c->lay.pf_gates);
   float *y_all = c->at<float>(c->lay.pf_y);
   hipError_t e;
+  if (int rc = c->check_waits()) return rc;
   if (!c->clock_running) { c->clock_running = true; c->t0 = std::chrono::steady_clock::now(); }
 
   // --- true routing of every prompt token, one kernel per micro-batch of at most max_batch tokens
   TimedSpan *sp_route = c->open_span(0, c->compute);
+  const bool pair_kernel = route_pair_supported(H, cfg.dtype);   // the fused kernel, asked for the true routing only
   for (int t0 = 0; t0 < P; t0 += MB) {
     const int nb = std::min(MB, P - t0);
+    if (pair_kernel) {
+      RoutePairArgs pa{};
+      pa.r = r + size_t(t0) * H;
+      pa.w_true = c->router_w[layer];
+      pa.gain_true = static_cast<const float *>(c->gain[layer]);
+      pa.z_true = c->zslot_set(0, c->route_parity);
+      pa.z_pred = c->zslot_set(1, c->route_parity);
+      pa.z_true_next = c->zslot_set(0, c->route_parity ^ 1);
+      pa.z_pred_next = c->zslot_set(1, c->route_parity ^ 1);
+      pa.arm_count = cfg.max_batch * E;
+      c->route_parity ^= 1;
+      pa.s_out = s_all + size_t(t0) * H;
+      pa.s_out_q = cfg.dtype == MOE_SPEC_BF16 ? sq_all + size_t(t0) * H : nullptr;
+      pa.true_ids = ids_all + size_t(t0) * k;
+      pa.true_gates = gates_all + size_t(t0) * k;
+      pa.diag = c->at<LayerDiag>(c->lay.diag) + layer;
+      pa.user_true_ids = true_ids ? true_ids + size_t(t0) * k : nullptr;
+      pa.user_true_gates = true_gates ? true_gates + size_t(t0) * k : nullptr;
+      pa.status = c->wait_status_dev;
+      pa.B = nb; pa.H = H; pa.E = E; pa.k = k;
+      pa.eps = cfg.rms_eps;
+      pa.bf16 = cfg.dtype == MOE_SPEC_BF16;
+      pa.spin_limit = c->spin_limit;
+      if ((e = launch_route_pair(pa, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+      c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
+      continue;
+    }
     RouteArgs ra{};
     ra.r = r + size_t(t0) * H;
     ra.w = c->router_w[layer];
