@@ -363,7 +363,9 @@ class Bench:
                             r = eng.advance(r, pout, pe[l], wl.res_a, wl.res_b, pbuf[l & 1])
             group = min(max(wl.slots // 2, 1), wl.n_experts)          # experts per launch pair of the prefill step
             n_pairs = 3 * L * ((wl.n_experts + group - 1) // group)
-            self.leg(f"{wl.name}/prefill", dict({"advance_kernel": 3 * (L - 1)},
+            micro = min(64, P)                                        # tokens per routing launch
+            self.leg(f"{wl.name}/prefill", dict({"advance_kernel": 3 * (L - 1),
+                                                 "route_pair_kernel": 3 * L * ((P + micro - 1) // micro)},
                                                 **({m: n_pairs for m in MFMA} if wl.dtype == "bf16" else {})))
             prompt_pass()
             torch.cuda.synchronize()
