@@ -515,10 +515,11 @@ hipError_t launch_route_pair_t(const RoutePairArgs &a, hipStream_t st) {
   const int chunks = (a.H + Packed<WT>::N - 1) / Packed<WT>::N;
   const int need1 = (chunks + kWave - 1) / kWave;              // per lane, one wavefront per row
   const int need4 = (chunks + 4 * kWave - 1) / (4 * kWave);    // four wavefronts per row
-  // One token: a workgroup per router row, E workgroups (measured on 128 experts of 2048 columns: 12.9 us per
+  // One token: a workgroup per router row, E workgroups (measured on 128 experts of 2048 columns: 11.4 us per
   // launch).  A batch: its tokens already fill the device, and every workgroup repeats its token's norm, top-k
   // and default-vector sum, so the more tokens, the more rows per workgroup: 4 up to about 512 workgroups per
-  // launch, 16 beyond (8 tokens x 128 experts: 13.5 us with 4 rows per workgroup, 14.4 with 8, 16.7 with 16;
+  // launch, 16 beyond (measured before the polls were thinned out, which took about another
+  // 0.5 us off each: 8 tokens x 128 experts: 13.5 us with 4 rows per workgroup, 14.4 with 8, 16.7 with 16;
   // 32 tokens: 28.6, 17.3, 17.3 us; 64 tokens: 53.8, 31.7, 21.2 us; 32 rows per workgroup: 21 to 22 us at all three).
   if (a.B > 1 && need1 <= 8) {
     const long wgs4 = long(a.B) * ((a.E + 3) / 4);
