@@ -19,6 +19,7 @@ namespace {
 constexpr int kMaxTokTile = 1;     // tokens a workgroup handles (one: see route_lds_bytes)
 
 struct FinishShared {
+  double keys[kMaxExperts];          // the token's logits, one thread having waited for each
   int rank[kMaxExperts];
   double top_z[kMaxTopK];
   double top_e[kMaxTopK];
@@ -32,22 +33,28 @@ template <int R>
 __device__ void finish_tokens(const RouteArgs &a, FinishShared &sh, int tid, int b_begin, int b_end) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int kSrcPerWave = kWave / (kRouteBlock / kWave);
+  static_assert(kMaxExperts == kRouteBlock, "one thread per candidate");
   if (tid == 0) sh.hits = 0;
+  // the other workgroups' logits need more than a microsecond to get here: no look before 0.4 us have passed
+  // (polls in flight hold up the stores they are waiting for)
+  __builtin_amdgcn_s_sleep(16);
   for (int b = b_begin; b < b_end; ++b) {
+    // Thread i waits for logit i and shares it through LDS: one look at every slot per workgroup.
+    // A logit that is not a number (a non-finite input row) sorts as minus infinity: comparisons
+    // with NaN are all false, ranks would collide, and slots of the top-k table would keep whatever
+    // the LDS held - ids far outside [0, E) that later kernels use as row indices.  With this the
+    // order (logit descending, index ascending) is total whatever the input, and ids stay in range.
+    double mine = -INFINITY;
+    if (tid < a.E) {
+      const double zi = __longlong_as_double(static_cast<long long>(await64(a.slots + size_t(b) * a.E + tid, a.spin_limit, a.status)));
+      mine = zi == zi ? zi : -INFINITY;
+    }
+    sh.keys[tid] = mine;
+    sh.rank[tid] = 0;
+    __syncthreads();
     double key[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int i = r * kWave + lane;
-      // A logit that is not a number (a non-finite input row) sorts as minus infinity: comparisons
-      // with NaN are all false, ranks would collide, and slots of the top-k table would keep whatever
-      // the LDS held - ids far outside [0, E) that later kernels use as row indices.  With this the
-      // order (logit descending, index ascending) is total whatever the input, and ids stay in range.
-      double zi = -INFINITY;
-      if (i < a.E) zi = __longlong_as_double(static_cast<long long>(await64(a.slots + size_t(b) * a.E + i, a.spin_limit, a.status)));
-      key[r] = zi == zi ? zi : -INFINITY;
-    }
-    for (int i = tid; i < kMaxExperts; i += kRouteBlock) sh.rank[i] = 0;
-    __syncthreads();
+    for (int r = 0; r < R; ++r) key[r] = sh.keys[r * kWave + lane];
     int cnt[R];
     rank_counts<R>(key, lane, wave * kSrcPerWave, (wave + 1) * kSrcPerWave, cnt);
 #pragma unroll
