@@ -84,7 +84,7 @@ __device__ __forceinline__ unsigned long long readlane(unsigned long long v, int
 // workgroup that calls it.
 template <int R>
 __device__ void select_ids(const RoutePairArgs &a, int stage, const unsigned long long *slots, int E, int k,
-                           SelectShared &sel, int tid) {
+                           SelectShared &sel, int tid, int32_t *post) {
   const int lane = tid & (kWave - 1), wave = tid / kWave;
   constexpr int kSrcPerWave = kWave / kWaves;
   // thread i waits for logit i (one look at every slot per workgroup, not one per wavefront) and shares it
@@ -137,22 +137,27 @@ __device__ void select_ids(const RoutePairArgs &a, int stage, const unsigned lon
       const int rk = (sel.cnt[0][i] + sel.cnt[1][i]) + (sel.cnt[2][i] + sel.cnt[3][i]);
       if (i < E && rk < k) { sel.top_z[rk] = unsortable(key[r]); sel.top_i[rk] = i; }
     }
+    // still in wavefront 0, whose own LDS writes it reads back in order: the ids go out to the host, if it waits
+    // for them, and the numerators of the k gates are formed, before the other wavefronts are let go
+    if (lane < k) {
+      if (post) post[lane] = sel.top_i[lane];
+      sel.top_e[lane] = exp(sel.top_z[lane] - sel.top_z[0]);
+    }
   }
   __syncthreads();
 }
 
 __device__ __forceinline__ void select_ids_any(const RoutePairArgs &a, int stage, const unsigned long long *slots,
-                                               int E, int k, SelectShared &sel, int tid) {
-  if (E <= kWave) select_ids<1>(a, stage, slots, E, k, sel, tid);
-  else if (E <= 2 * kWave) select_ids<2>(a, stage, slots, E, k, sel, tid);
-  else select_ids<4>(a, stage, slots, E, k, sel, tid);
+                                               int E, int k, SelectShared &sel, int tid, int32_t *post = nullptr) {
+  if (E <= kWave) select_ids<1>(a, stage, slots, E, k, sel, tid, post);
+  else if (E <= 2 * kWave) select_ids<2>(a, stage, slots, E, k, sel, tid, post);
+  else select_ids<4>(a, stage, slots, E, k, sel, tid, post);
 }
 
-// Softmax over the k selected logits: sel.top_e[j] = exp(z_j - z_0); returns their sum (the same in every
-// thread), so that gate j is top_e[j] / sum.
+// Softmax over the k selected logits: select_ids left sel.top_e[j] = exp(z_j - z_0); returns their sum (the same
+// in every thread), so that gate j is top_e[j] / sum.
 __device__ __forceinline__ double select_gates(int k, SelectShared &sel, int tid) {
-  if (tid < k) sel.top_e[tid] = exp(sel.top_z[tid] - sel.top_z[0]);
-  __syncthreads();
+  (void)tid;
   double denom = 0.0;
   for (int q = 0; q < k; ++q) denom += sel.top_e[q];
   return denom;
@@ -446,8 +451,8 @@ __global__ __launch_bounds__(kBlock) void route_pair_kernel(const RoutePairArgs 
   if (wg != 0) return;
 
   // ---- (E^_{l+1}, G^_{l+1})
-  select_ids_any(a, 9, a.z_pred + size_t(b) * E, E, k, sh.sel, tid);
-  if (tid < k && a.mb_next) a.mb_next->ids[size_t(b) * k + tid] = sh.sel.top_i[tid];   // the host starts the prefetch on these
+  select_ids_any(a, 9, a.z_pred + size_t(b) * E, E, k, sh.sel, tid,
+                 a.mb_next ? a.mb_next->ids + size_t(b) * k : nullptr);                  // the host starts the prefetch on these
   const double denom_next = select_gates(k, sh.sel, tid);
   STAGE(10);
   if (tid < k) {
