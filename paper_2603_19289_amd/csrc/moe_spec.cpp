@@ -802,8 +802,39 @@ int layer_step_impl(moe_spec_ctx *c, int layer, const void *r_dev, int batch, vo
   ra.eps = cfg.rms_eps;
   ra.bf16 = cfg.dtype == MOE_SPEC_BF16;
   ra.spec = 0;
-  c->prep_route(ra);
-  if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+  if (!cfg.diagnostics && route_pair_supported(H, cfg.dtype)) {
+    // the fused kernel, asked for the true routing only (it is the faster of the two at that); the prediction
+    // below comes from the estimator or the baseline signal and keeps its own launches
+    RoutePairArgs ta{};
+    ta.r = ra.r;
+    ta.w_true = ra.w;
+    ta.gain_true = ra.gain;
+    ta.z_true = c->zslot_set(0, c->route_parity);
+    ta.z_pred = c->zslot_set(1, c->route_parity);
+    ta.z_true_next = c->zslot_set(0, c->route_parity ^ 1);
+    ta.z_pred_next = c->zslot_set(1, c->route_parity ^ 1);
+    ta.arm_count = cfg.max_batch * E;
+    c->route_parity ^= 1;
+    ta.s_out = ra.vec_out;
+    ta.s_out_q = ra.vec_out_q;
+    ta.true_ids = ra.ids_out;
+    ta.true_gates = ra.gates_out;
+    ta.true_gates64 = ra.gates64_out;
+    ta.cmp_ids = ra.cmp_ids;
+    ta.diag = ra.diag;
+    ta.user_true_ids = ra.user_ids;
+    ta.user_true_gates = ra.user_gates;
+    ta.mb_true = ra.mailbox;
+    ta.status = c->wait_status_dev;
+    ta.B = batch; ta.H = H; ta.E = E; ta.k = k;
+    ta.eps = cfg.rms_eps;
+    ta.bf16 = ra.bf16;
+    ta.spin_limit = c->spin_limit;
+    if ((e = launch_route_pair(ta, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+  } else {
+    c->prep_route(ra);
+    if ((e = launch_route(ra, cfg.dtype, c->compute)) != hipSuccess) return c->hip_fail(e, "routing kernel");
+  }
   c->st.hbm_bytes_algorithmic += int64_t(E) * H * wbytes;
 
   // --- prediction for layer l+1 from the quasi-hidden state
